@@ -1,0 +1,208 @@
+"""CPU oracle: the plain definition of normalized-adjacency propagation, in double.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the GPU package imports this; only tests, the smoke
+check and the benchmark's CPU-baseline leg do.  The arithmetic is in `e2eg_oracle.c`
+(plain C, built with gcc into `libe2eg_oracle.so`); this file marshals numpy arrays and
+strings the layers together in the order the paper writes them:
+
+    H(0) = X,  H(l+1) = A^ H(l)   for l = 0..K-1          (Section 3.1, LightGCN matrix form)
+    G(K) = dL/dH(K),  G(l) = A^T G(l+1) [+ dL/dH(l) direct] (Appendix A, GNN backprop factor)
+
+with A^ = D~^-1/2 (A + I) D~^-1/2 (Section 3, "Notation").
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "e2eg_oracle.c")
+_LIB = os.path.join(_HERE, "libe2eg_oracle.so")
+_lib = None
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.e2eg_oracle_max_threads.restype = ctypes.c_int32
+        lib.e2eg_oracle_set_threads.argtypes = [ctypes.c_int32]
+        lib.e2eg_oracle_build_csr.restype = ctypes.c_int64
+        lib.e2eg_oracle_build_csr.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _i32p, _i32p,
+                                              ctypes.c_int32, _i64p, _i32p]
+        lib.e2eg_oracle_normalize.argtypes = [ctypes.c_int64, _i64p, _i64p, _f64p]
+        lib.e2eg_oracle_propagate_layer.argtypes = [ctypes.c_int64, _i64p, _i32p, ctypes.c_int64, _f64p, _f64p]
+        lib.e2eg_oracle_propagate_layer_transposed.argtypes = lib.e2eg_oracle_propagate_layer.argtypes
+        lib.e2eg_oracle_propagate_rows.argtypes = [ctypes.c_int64, _i64p, _i64p, _i32p, ctypes.c_int64,
+                                                   _f64p, _f64p]
+        lib.e2eg_oracle_transform_fwd.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p,
+                                                  ctypes.c_int32, _f64p, _f64p]
+        lib.e2eg_oracle_transform_bwd.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p,
+                                                  _f64p, _f64p, ctypes.c_int32, _f64p, _f64p]
+        _lib = lib
+    return _lib
+
+
+def _p(a, t):
+    return a.ctypes.data_as(t)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def max_threads() -> int:
+    return int(_load().e2eg_oracle_max_threads())
+
+
+def set_threads(t: int) -> None:
+    _load().e2eg_oracle_set_threads(int(t))
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bf16 bit patterns (uint16) as doubles."""
+    u = _c(bits, np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def as_f64(x: np.ndarray) -> np.ndarray:
+    """The exact values of an input array: fp32 values, or bf16 bit patterns if uint16."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return bf16_bits_to_f64(x)
+    return _c(x, np.float64)
+
+
+def build_csr(n_users, n_items, users, items, add_self_loops=True):
+    """Canonical CSR of A~ = A + I (of A if not add_self_loops).  -> (row_ptr int64[n+1],
+    col_idx int32[nnz])."""
+    users = _c(users, np.int32)
+    items = _c(items, np.int32)
+    if users.shape != items.shape or users.ndim != 1:
+        raise ValueError("users/items must be 1-D arrays of equal length")
+    n = int(n_users) + int(n_items)
+    E = users.size
+    row_ptr = np.zeros(n + 1, dtype=np.int64)
+    col = np.empty(max(1, 2 * E + n), dtype=np.int32)
+    nnz = _load().e2eg_oracle_build_csr(n_users, n_items, E, _p(users, _i32p), _p(items, _i32p),
+                                        1 if add_self_loops else 0, _p(row_ptr, _i64p), _p(col, _i32p))
+    if nnz < 0:
+        raise ValueError("edge id out of range")
+    return row_ptr, col[:nnz].copy()
+
+
+def normalize(row_ptr):
+    """-> (deg int64[n] = d~_i, dinv_sqrt float64[n] = d~_i^-1/2)."""
+    row_ptr = _c(row_ptr, np.int64)
+    n = row_ptr.size - 1
+    deg = np.empty(n, dtype=np.int64)
+    dinv = np.empty(n, dtype=np.float64)
+    _load().e2eg_oracle_normalize(n, _p(row_ptr, _i64p), _p(deg, _i64p), _p(dinv, _f64p))
+    return deg, dinv
+
+
+def propagate_layer(row_ptr, col_idx, X):
+    """Y = A^ X for one layer (gather over rows)."""
+    row_ptr = _c(row_ptr, np.int64)
+    col_idx = _c(col_idx, np.int32)
+    X = _c(X, np.float64)
+    n, F = X.shape
+    assert row_ptr.size == n + 1
+    Y = np.empty_like(X)
+    _load().e2eg_oracle_propagate_layer(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), F, _p(X, _f64p),
+                                        _p(Y, _f64p))
+    return Y
+
+
+def propagate_layer_transposed(row_ptr, col_idx, G):
+    """A^T G for one layer (scatter over the rows of the forward CSR)."""
+    row_ptr = _c(row_ptr, np.int64)
+    col_idx = _c(col_idx, np.int32)
+    G = _c(G, np.float64)
+    n, F = G.shape
+    assert row_ptr.size == n + 1
+    out = np.empty_like(G)
+    _load().e2eg_oracle_propagate_layer_transposed(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), F,
+                                                   _p(G, _f64p), _p(out, _f64p))
+    return out
+
+
+def propagate_rows(row_ptr, col_idx, X, rows):
+    """(A^ X)[rows] computed row by row."""
+    row_ptr = _c(row_ptr, np.int64)
+    col_idx = _c(col_idx, np.int32)
+    X = _c(X, np.float64)
+    rows = _c(rows, np.int64)
+    F = X.shape[1]
+    Y = np.empty((rows.size, F), dtype=np.float64)
+    _load().e2eg_oracle_propagate_rows(rows.size, _p(rows, _i64p), _p(row_ptr, _i64p), _p(col_idx, _i32p),
+                                       F, _p(X, _f64p), _p(Y, _f64p))
+    return Y
+
+
+def propagate_fwd(row_ptr, col_idx, X0, K):
+    """[H(1), ..., H(K)] with H(0) = X0 (fp32 values or bf16 bit patterns), no rounding in
+    between."""
+    H = as_f64(X0)
+    layers = []
+    for _ in range(K):
+        H = propagate_layer(row_ptr, col_idx, H)
+        layers.append(H)
+    return layers
+
+
+def propagate_bwd(row_ptr, col_idx, gHK, K, g_layers=None):
+    """dL/dH(0) given dL/dH(K) and optional direct terms dL/dH(1..K-1) (list of K-1
+    arrays, entry l-1 for layer l)."""
+    G = as_f64(gHK)
+    for l in range(K - 1, -1, -1):
+        G = propagate_layer_transposed(row_ptr, col_idx, G)
+        if g_layers is not None and l >= 1:
+            G = G + as_f64(g_layers[l - 1])
+    return G
+
+
+def transform_fwd(P, W, relu=True):
+    """Z = P W and H = max(Z, 0) (H = Z if not relu).  -> (Z, H)."""
+    P = as_f64(P)
+    W = as_f64(W)
+    n, Fin = P.shape
+    assert W.shape[0] == Fin
+    Fout = W.shape[1]
+    Z = np.empty((n, Fout), dtype=np.float64)
+    H = np.empty((n, Fout), dtype=np.float64)
+    _load().e2eg_oracle_transform_fwd(n, Fin, Fout, _p(P, _f64p), _p(W, _f64p), 1 if relu else 0,
+                                      _p(Z, _f64p), _p(H, _f64p))
+    return Z, H
+
+
+def transform_bwd(P, W, mask, gH, relu=True):
+    """dP = dZ W^T, dW = P^T dZ with dZ = gH * [mask > 0] (dZ = gH if not relu)."""
+    P = as_f64(P)
+    W = as_f64(W)
+    mask = as_f64(mask)
+    gH = as_f64(gH)
+    n, Fin = P.shape
+    Fout = W.shape[1]
+    dP = np.empty((n, Fin), dtype=np.float64)
+    dW = np.empty((Fin, Fout), dtype=np.float64)
+    _load().e2eg_oracle_transform_bwd(n, Fin, Fout, _p(P, _f64p), _p(W, _f64p), _p(mask, _f64p),
+                                      _p(gH, _f64p), 1 if relu else 0, _p(dP, _f64p), _p(dW, _f64p))
+    return dP, dW

@@ -1,0 +1,212 @@
+/*
+ * CPU oracle for normalized-adjacency message passing on a user-item graph.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, double-precision
+ * statement of what the GPU library must compute.  Only the test-suite, the
+ * smoke check and the benchmark's CPU-baseline leg may call it; the product
+ * path never does.  It shares no source, header, table or helper with the GPU
+ * library.
+ *
+ * What is computed, and where the paper defines it:
+ *   - A: n x n adjacency with A_ij > 0 iff (i,j) is an edge (Section 3,
+ *     "Notation").  The graph is an undirected user-item graph: node u for
+ *     user u, node n_users + i for item i; a distinct input pair (u,i) gives
+ *     A[u][nu+i] = A[nu+i][u] = 1.  Repeated pairs are one edge.
+ *   - A~ = A + I, D~ = D + I with D = diag(A 1), A^ = D~^-1/2 A~ D~^-1/2
+ *     (Section 3, "Notation").
+ *   - LightGCN propagation H(l+1) = A^ H(l) (Section 3.1, matrix form of the
+ *     LightGCN update), K layers, K = number of sampled hops (Section 5).
+ *   - Without the self-loop augmentation the same code evaluates the per-node
+ *     LightGCN update, weights 1/(sqrt|N(u)| sqrt|N(i)|) (Section 3.1).
+ *   - Backward: the transpose-Jacobian of the linear map, G(l) = A^T G(l+1)
+ *     (Appendix A, the "GNN backprop" factor of the chain rule; Section 4.3.2,
+ *     the J^T dL/dF_gnn terms of the multi-task gradient).  Written as a
+ *     scatter over the forward CSR so that it is the transpose by construction
+ *     and assumes no symmetry.
+ *   - Dense per-layer update Z = P W, H' = max(Z, 0): the update function psi of
+ *     the generic message-passing layer with the W, sigma of the GraphSAGE
+ *     layer (Section 3 and Section 3.1), and its backward.
+ *
+ * All floating point is IEEE double; sums run in CSR (ascending column) order.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int32_t e2eg_oracle_max_threads(void) {
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void e2eg_oracle_set_threads(int32_t t) {
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
+
+static int cmp_u64(const void* a, const void* b) {
+    uint64_t x = *(const uint64_t*)a, y = *(const uint64_t*)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Structure of A~ (or of A when add_self_loops == 0) in canonical CSR:
+ * rows in node order, columns strictly ascending.  Built the obvious way:
+ * list every (row, col) entry, sort, drop repeats.
+ * row_ptr has n+1 entries; col_idx has room for 2*n_edges + n entries.
+ * Returns nnz, or -1 on an out-of-range id / allocation failure.
+ */
+int64_t e2eg_oracle_build_csr(int32_t n_users, int32_t n_items, int64_t n_edges,
+                              const int32_t* users, const int32_t* items,
+                              int32_t add_self_loops, int64_t* row_ptr, int32_t* col_idx) {
+    int64_t n = (int64_t)n_users + n_items;
+    int64_t cap = 2 * n_edges + (add_self_loops ? n : 0);
+    uint64_t* key = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(cap > 0 ? cap : 1));
+    if (!key) return -1;
+    int64_t m = 0;
+    for (int64_t e = 0; e < n_edges; ++e) {
+        int64_t u = users[e], i = items[e];
+        if (u < 0 || u >= n_users || i < 0 || i >= n_items) { free(key); return -1; }
+        uint64_t a = (uint64_t)u, b = (uint64_t)(n_users + i);
+        key[m++] = (a << 32) | b;   /* A[u][nu+i] */
+        key[m++] = (b << 32) | a;   /* A[nu+i][u] */
+    }
+    if (add_self_loops)
+        for (int64_t v = 0; v < n; ++v) key[m++] = ((uint64_t)v << 32) | (uint64_t)v;  /* + I */
+    qsort(key, (size_t)m, sizeof(uint64_t), cmp_u64);
+    int64_t nnz = 0;
+    for (int64_t r = 0; r <= n; ++r) row_ptr[r] = 0;
+    for (int64_t k = 0; k < m; ++k) {
+        if (k > 0 && key[k] == key[k - 1]) continue;   /* repeated pair: one edge */
+        col_idx[nnz++] = (int32_t)(key[k] & 0xffffffffu);
+        row_ptr[(key[k] >> 32) + 1] += 1;
+    }
+    for (int64_t r = 0; r < n; ++r) row_ptr[r + 1] += row_ptr[r];
+    free(key);
+    return nnz;
+}
+
+/* d~_i = sum_j A~_ij = number of stored entries in row i;  s_i = d~_i^-1/2 (0 for an
+ * empty row, which can only occur without self-loops). */
+void e2eg_oracle_normalize(int64_t n, const int64_t* row_ptr, int64_t* deg, double* dinv_sqrt) {
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t d = row_ptr[i + 1] - row_ptr[i];
+        deg[i] = d;
+        dinv_sqrt[i] = d > 0 ? 1.0 / sqrt((double)d) : 0.0;
+    }
+}
+
+/* A^_ij for a stored entry: A~_ij / sqrt(d~_i d~_j) with A~_ij = 1. */
+static inline double a_hat(const int64_t* row_ptr, int64_t i, int64_t j) {
+    double di = (double)(row_ptr[i + 1] - row_ptr[i]);
+    double dj = (double)(row_ptr[j + 1] - row_ptr[j]);
+    return 1.0 / sqrt(di * dj);
+}
+
+/* One layer, gather form:  Y_i = sum_j A^_ij X_j.   X, Y: [n][F] row-major doubles. */
+void e2eg_oracle_propagate_layer(int64_t n, const int64_t* row_ptr, const int32_t* col_idx,
+                                 int64_t F, const double* X, double* Y) {
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n; ++i) {
+        double* y = Y + i * F;
+        for (int64_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            double a = a_hat(row_ptr, i, j);
+            const double* x = X + j * F;
+            for (int64_t f = 0; f < F; ++f) y[f] += a * x[f];
+        }
+    }
+}
+
+/* Same, for a chosen list of rows only:  Y[r] = sum_j A^_{rows[r], j} X_j. */
+void e2eg_oracle_propagate_rows(int64_t n_rows, const int64_t* rows, const int64_t* row_ptr,
+                                const int32_t* col_idx, int64_t F, const double* X, double* Y) {
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t i = rows[r];
+        double* y = Y + r * F;
+        for (int64_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            double a = a_hat(row_ptr, i, j);
+            const double* x = X + j * F;
+            for (int64_t f = 0; f < F; ++f) y[f] += a * x[f];
+        }
+    }
+}
+
+/*
+ * One layer of the backward, scatter form:  G_j += A^_ij Gnext_i for every stored (i,j),
+ * i.e. G = A^T Gnext whatever the structure.  Threads split the feature columns, so every
+ * element sees the same sequence of additions as in a single-threaded run.
+ */
+void e2eg_oracle_propagate_layer_transposed(int64_t n, const int64_t* row_ptr,
+                                            const int32_t* col_idx, int64_t F,
+                                            const double* Gnext, double* G) {
+    int64_t nblk = (F + 7) / 8;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < nblk; ++b) {
+        int64_t f0 = b * 8, f1 = f0 + 8 < F ? f0 + 8 : F;
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t f = f0; f < f1; ++f) G[i * F + f] = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            const double* g = Gnext + i * F;
+            for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+                int64_t j = col_idx[p];
+                double a = a_hat(row_ptr, i, j);
+                double* o = G + j * F;
+                for (int64_t f = f0; f < f1; ++f) o[f] += a * g[f];
+            }
+        }
+    }
+}
+
+/* Dense update:  Z = P W  ([n][Fin] x [Fin][Fout]),  H = relu ? max(Z, 0) : Z. */
+void e2eg_oracle_transform_fwd(int64_t n, int64_t Fin, int64_t Fout, const double* P,
+                               const double* W, int32_t relu, double* Z, double* H) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t o = 0; o < Fout; ++o) {
+            double z = 0.0;
+            for (int64_t c = 0; c < Fin; ++c) z += P[i * Fin + c] * W[c * Fout + o];
+            Z[i * Fout + o] = z;
+            H[i * Fout + o] = (relu && !(z > 0.0)) ? 0.0 : z;
+        }
+}
+
+/*
+ * Backward of the dense update.  dZ = gH * [mask > 0] when relu (mask: [n][Fout], the
+ * caller passes Z or H; both have the same sign pattern), else dZ = gH.
+ * dP = dZ W^T,  dW = P^T dZ.
+ */
+void e2eg_oracle_transform_bwd(int64_t n, int64_t Fin, int64_t Fout, const double* P,
+                               const double* W, const double* mask, const double* gH,
+                               int32_t relu, double* dP, double* dW) {
+    double* dZ = (double*)malloc(sizeof(double) * (size_t)(n * Fout > 0 ? n * Fout : 1));
+    for (int64_t k = 0; k < n * Fout; ++k) dZ[k] = (relu && !(mask[k] > 0.0)) ? 0.0 : gH[k];
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t c = 0; c < Fin; ++c) {
+            double s = 0.0;
+            for (int64_t o = 0; o < Fout; ++o) s += dZ[i * Fout + o] * W[c * Fout + o];
+            dP[i * Fin + c] = s;
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < Fin; ++c)
+        for (int64_t o = 0; o < Fout; ++o) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i) s += P[i * Fin + c] * dZ[i * Fout + o];
+            dW[c * Fout + o] = s;
+        }
+    free(dZ);
+}

@@ -1,0 +1,474 @@
+"""Pins for the CPU oracle: it is checked against things that are not itself.
+
+ * a dense A^ assembled literally from the definitions of Section 3 ("Notation"):
+   A from the edge set, A~ = A + I, D = diag(A 1), D~ = D + I, A^ = D~^-1/2 A~ D~^-1/2;
+ * closed forms that follow from that definition on graphs solvable by hand
+   (values in tests/golden/);
+ * invariants: symmetry, spectrum in (-1, 1] (L^ = I - A^ is a normalized Laplacian),
+   D~^1/2 1 a fixed point;
+ * the backward being the transpose (dense A^T G, adjoint identity, finite differences),
+   also on a deliberately non-symmetric structure;
+ * an independent library evaluation (scipy.sparse);
+ * the per-node LightGCN update of Section 3.1 written as python loops (no self-loop variant).
+"""
+import os
+
+import numpy as np
+import pytest
+
+from workloads import make_config, uniform_bipartite
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- dense definition
+def dense_ahat(n_users, n_items, users, items, self_loops=True):
+    """A^ from Section 3 "Notation", dense and literal."""
+    n = n_users + n_items
+    A = np.zeros((n, n))
+    for u, i in zip(users, items):          # A_ij > 0 iff (i,j) in E, undirected
+        A[u, n_users + i] = 1.0
+        A[n_users + i, u] = 1.0
+    I = np.eye(n)
+    D = np.diag(A @ np.ones(n))
+    if self_loops:
+        At, Dt = A + I, D + I
+        assert np.array_equal(np.diag(Dt), At @ np.ones(n))   # D + I == diag(A~ 1)
+    else:
+        At, Dt = A, D
+    d = np.diag(Dt)
+    s = np.where(d > 0, 1.0 / np.sqrt(np.where(d > 0, d, 1.0)), 0.0)
+    return np.diag(s) @ At @ np.diag(s), At
+
+
+def small_graph(seed, nu=13, ni=9, ne=40, dup=True):
+    rng = np.random.default_rng(seed)
+    u, i = uniform_bipartite(nu, ni, ne, seed)
+    if dup:  # repeated pairs must collapse to one edge
+        k = rng.integers(0, ne, size=7)
+        u = np.concatenate([u, u[k]])
+        i = np.concatenate([i, i[k]])
+    return nu, ni, u, i
+
+
+def relerr(a, b):
+    return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+# ---------------------------------------------------------------- structure
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("self_loops", [True, False])
+def test_csr_matches_dense_pattern(oracle, seed, self_loops):
+    nu, ni, u, i = small_graph(seed)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i, add_self_loops=self_loops)
+    _, At = dense_ahat(nu, ni, u, i, self_loops)
+    n = nu + ni
+    assert row_ptr[0] == 0 and row_ptr[-1] == col.size == int((At > 0).sum())
+    for r in range(n):
+        cols = col[row_ptr[r]:row_ptr[r + 1]]
+        assert np.array_equal(cols, np.flatnonzero(At[r] > 0))   # ascending, no repeats
+
+
+def test_csr_structure_config1(oracle):
+    c = make_config(1, features=False)
+    nu, ni = c["n_users"], c["n_items"]
+    n, E = c["n"], c["n_edges"]
+    row_ptr, col = oracle.build_csr(nu, ni, c["users"], c["items"])
+    assert col.size == 2 * E + n == 43_000
+    deg = np.diff(row_ptr)
+    assert (deg >= 1).all()
+    assert deg[:nu].sum() - nu == E and deg[nu:].sum() - ni == E
+    for r in range(n):
+        cols = col[row_ptr[r]:row_ptr[r + 1]]
+        assert (np.diff(cols) > 0).all()
+        if r < nu:   # user row: itself first, then items
+            assert cols[0] == r and (cols[1:] >= nu).all()
+        else:        # item row: users, itself last
+            assert cols[-1] == r and (cols[:-1] < nu).all()
+    # structural symmetry
+    rows = np.repeat(np.arange(n), deg)
+    fwd = set(zip(rows.tolist(), col.tolist()))
+    assert all((c_, r_) in fwd for r_, c_ in fwd)
+
+
+def test_build_csr_rejects_bad_ids(oracle):
+    with pytest.raises(ValueError):
+        oracle.build_csr(3, 2, np.array([0, 3]), np.array([0, 1]))
+    with pytest.raises(ValueError):
+        oracle.build_csr(3, 2, np.array([0, 1]), np.array([0, -1]))
+
+
+def test_normalize_degrees(oracle):
+    nu, ni, u, i = small_graph(5)
+    row_ptr, _ = oracle.build_csr(nu, ni, u, i)
+    deg, dinv = oracle.normalize(row_ptr)
+    _, At = dense_ahat(nu, ni, u, i)
+    assert np.array_equal(deg, (At @ np.ones(nu + ni)).astype(np.int64))
+    assert np.allclose(dinv * dinv * deg, 1.0, rtol=1e-15)
+
+
+# ---------------------------------------------------------------- forward vs dense
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+@pytest.mark.parametrize("K", [1, 2, 4])
+def test_forward_matches_dense_small(oracle, seed, K):
+    nu, ni, u, i = small_graph(seed)
+    Ahat, _ = dense_ahat(nu, ni, u, i)
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((nu + ni, 5))
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    layers = oracle.propagate_fwd(row_ptr, col, X, K)
+    ref = X
+    for k in range(K):
+        ref = Ahat @ ref
+        assert relerr(layers[k], ref) < 1e-12
+
+
+def test_forward_matches_dense_config1(oracle):
+    c = make_config(1)
+    Ahat, _ = dense_ahat(c["n_users"], c["n_items"], c["users"], c["items"])
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    layers = oracle.propagate_fwd(row_ptr, col, c["X0"], c["K"])
+    X = c["X0"].astype(np.float64)
+    assert relerr(layers[0], Ahat @ X) < 1e-12
+    assert relerr(layers[1], Ahat @ (Ahat @ X)) < 1e-12
+
+
+def test_forward_matches_dense_hypothesis(oracle):
+    hyp = pytest.importorskip("hypothesis")
+    st = hyp.strategies
+
+    @hyp.settings(max_examples=60, deadline=None)
+    @hyp.given(nu=st.integers(1, 7), ni=st.integers(1, 6), data=st.data())
+    def run(nu, ni, data):
+        ne = data.draw(st.integers(0, 25))
+        u = np.array(data.draw(st.lists(st.integers(0, nu - 1), min_size=ne, max_size=ne)), dtype=np.int32)
+        i = np.array(data.draw(st.lists(st.integers(0, ni - 1), min_size=ne, max_size=ne)), dtype=np.int32)
+        Ahat, _ = dense_ahat(nu, ni, u, i)
+        X = np.arange((nu + ni) * 3, dtype=np.float64).reshape(nu + ni, 3) - 4.0
+        row_ptr, col = oracle.build_csr(nu, ni, u, i)
+        out = oracle.propagate_fwd(row_ptr, col, X, 2)[-1]
+        assert relerr(out, Ahat @ Ahat @ X) < 1e-12
+
+    run()
+
+
+def test_planted_mistakes_are_caught(oracle):
+    """The dense pin has teeth: operators that differ from A^ by one plausible slip
+    (D for D~, no self-loop, row normalisation, one-sided scaling) do not match."""
+    nu, ni, u, i = small_graph(21)
+    n = nu + ni
+    Ahat, At = dense_ahat(nu, ni, u, i)
+    A = At - np.eye(n)
+    d = A.sum(1)
+    dt = d + 1
+    wrong = [
+        np.diag(dt ** -0.5) @ A @ np.diag(dt ** -0.5),                 # forgot + I in A~
+        np.diag(np.maximum(d, 1) ** -0.5) @ At @ np.diag(np.maximum(d, 1) ** -0.5),  # D, not D~
+        np.diag(1.0 / dt) @ At,                                        # row normalisation
+        np.diag(dt ** -0.5) @ At,                                      # one-sided
+    ]
+    X = np.random.default_rng(0).standard_normal((n, 4))
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    out = oracle.propagate_layer(row_ptr, col, X)
+    assert relerr(out, Ahat @ X) < 1e-12
+    for M in wrong:
+        assert relerr(out, M @ X) > 1e-3
+
+
+# ---------------------------------------------------------------- closed forms
+def _ahat_from_oracle(oracle, nu, ni, u, i, self_loops=True):
+    """A^ column by column: propagate the identity."""
+    row_ptr, col = oracle.build_csr(nu, ni, np.asarray(u, np.int32), np.asarray(i, np.int32),
+                                    add_self_loops=self_loops)
+    return oracle.propagate_layer(row_ptr, col, np.eye(nu + ni))
+
+
+def _golden(name):
+    vals = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split("=")
+                vals[k.strip()] = float(v)
+    return vals
+
+
+def test_closed_form_no_edges(oracle):
+    M = _ahat_from_oracle(oracle, 3, 2, [], [])
+    assert np.array_equal(M, np.eye(5))          # A^ = I: every layer returns its input
+
+
+def test_closed_form_single_edge(oracle):
+    M = _ahat_from_oracle(oracle, 1, 1, [0], [0])
+    assert np.allclose(M, 0.5, rtol=0, atol=1e-16)   # pair average, idempotent
+    assert np.allclose(M @ M, M)
+
+
+def test_closed_form_star_golden(oracle):
+    g = _golden("star_m5.txt")
+    m = 5
+    M = _ahat_from_oracle(oracle, m, 1, list(range(m)), [0] * m)
+    item = m
+    assert abs(M[item, item] - g["item_item"]) < 1e-12
+    for u in range(m):
+        assert abs(M[item, u] - g["item_user"]) < 1e-12
+        assert abs(M[u, item] - g["item_user"]) < 1e-12
+        assert abs(M[u, u] - g["user_user"]) < 1e-12
+    ev = np.linalg.eigvalsh(M)
+    assert abs(ev.min() - g["lambda_min"]) < 1e-12 and abs(ev.max() - g["lambda_max"]) < 1e-12
+
+
+@pytest.mark.parametrize("m", [1, 2, 7, 30])
+def test_closed_form_star(oracle, m):
+    M = _ahat_from_oracle(oracle, m, 1, list(range(m)), [0] * m)
+    assert np.isclose(M[m, m], 1.0 / (m + 1), rtol=1e-14)
+    assert np.allclose(M[m, :m], 1.0 / np.sqrt(2.0 * (m + 1)), rtol=1e-14)
+    assert np.allclose(np.diag(M)[:m], 0.5, rtol=1e-14)
+    off = M[:m, :m] - np.diag(np.diag(M)[:m])
+    assert np.array_equal(off, np.zeros_like(off))
+
+
+@pytest.mark.parametrize("a,b", [(2, 3), (4, 4), (1, 6)])
+def test_closed_form_complete_bipartite(oracle, a, b):
+    u, i = np.meshgrid(np.arange(a), np.arange(b), indexing="ij")
+    M = _ahat_from_oracle(oracle, a, b, u.ravel(), i.ravel())
+    assert np.allclose(np.diag(M)[:a], 1.0 / (b + 1), rtol=1e-14)
+    assert np.allclose(np.diag(M)[a:], 1.0 / (a + 1), rtol=1e-14)
+    assert np.allclose(M[:a, a:], 1.0 / np.sqrt((a + 1.0) * (b + 1.0)), rtol=1e-14)
+    assert np.array_equal(M[:a, :a] - np.diag(np.diag(M)[:a]), np.zeros((a, a)))
+
+
+@pytest.mark.parametrize("d", [1, 2, 3])
+def test_closed_form_regular(oracle, d):
+    """d-regular bipartite (circulant): A^ = (A + I) / (d + 1)."""
+    m = 6
+    u = np.repeat(np.arange(m), d)
+    i = (u + np.tile(np.arange(d), m)) % m
+    M = _ahat_from_oracle(oracle, m, m, u, i)
+    _, At = dense_ahat(m, m, u, i)
+    assert np.allclose(M, At / (d + 1.0), rtol=1e-14, atol=0)
+
+
+# ---------------------------------------------------------------- invariants
+@pytest.mark.parametrize("seed", [31, 32])
+def test_invariants_small(oracle, seed):
+    nu, ni, u, i = small_graph(seed, nu=40, ni=25, ne=300)
+    M = _ahat_from_oracle(oracle, nu, ni, u, i)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    deg, dinv = oracle.normalize(row_ptr)
+    assert np.allclose(M, M.T, rtol=1e-15, atol=0)               # symmetric
+    nz = M[M != 0]
+    assert (nz > 0).all() and (nz <= 1).all()
+    assert np.allclose(np.diag(M), 1.0 / deg, rtol=1e-14)        # A^_ii = 1 / d~_i
+    ev = np.linalg.eigvalsh(M)
+    assert ev.max() <= 1 + 1e-12 and ev.min() > -1               # spectrum in (-1, 1]
+    assert abs(ev.max() - 1.0) < 1e-12
+    v = np.sqrt(deg.astype(np.float64))[:, None]                 # D~^1/2 1
+    for out in oracle.propagate_fwd(row_ptr, col, v, 5):
+        assert np.allclose(out, v, rtol=1e-13)
+
+
+def test_invariants_config2(oracle):
+    """Fixed point and contraction on the 2 M-edge power-law graph (O(nnz) checks)."""
+    c = make_config(2, features=False)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    assert col.size == 2 * c["n_edges"] + c["n"]
+    deg, _ = oracle.normalize(row_ptr)
+    v = np.sqrt(deg.astype(np.float64))
+    x = np.random.default_rng(3).standard_normal(c["n"])
+    X = np.stack([v, x], axis=1)
+    out = oracle.propagate_fwd(row_ptr, col, X, 3)
+    for k in range(3):
+        assert np.allclose(out[k][:, 0], v, rtol=1e-12)
+    norms = [np.linalg.norm(x)] + [np.linalg.norm(o[:, 1]) for o in out]
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(norms, norms[1:]))   # ||A^ x|| <= ||x||
+
+
+def test_scipy_cross_check_config2(oracle):
+    sp = pytest.importorskip("scipy.sparse")
+    c = make_config(2)
+    nu, ni, n = c["n_users"], c["n_items"], c["n"]
+    u = c["users"].astype(np.int64)
+    i = c["items"].astype(np.int64) + nu
+    A = sp.coo_matrix((np.ones(2 * u.size), (np.concatenate([u, i]), np.concatenate([i, u]))), shape=(n, n)).tocsr()
+    A.data[:] = 1.0
+    At = A + sp.identity(n, format="csr")
+    s = 1.0 / np.sqrt(np.asarray(At.sum(1)).ravel())
+    Ahat = sp.diags(s) @ At @ sp.diags(s)
+    X = c["X0"][:, :8].astype(np.float64)
+    row_ptr, col = oracle.build_csr(nu, ni, c["users"], c["items"])
+    got = oracle.propagate_fwd(row_ptr, col, X, 3)[-1]
+    ref = Ahat @ (Ahat @ (Ahat @ X))
+    scale = abs(Ahat) @ (abs(Ahat) @ (abs(Ahat) @ np.abs(X)))
+    assert (np.abs(got - ref) / (scale + 1e-300)).max() < 1e-12
+    G = c["gY"][:, :8].astype(np.float64)
+    gb = oracle.propagate_bwd(row_ptr, col, G, 2)
+    refb = Ahat.T @ (Ahat.T @ G)
+    assert relerr(gb, refb) < 1e-12
+
+
+# ---------------------------------------------------------------- backward
+@pytest.mark.parametrize("seed", [41, 42])
+@pytest.mark.parametrize("K", [1, 3])
+def test_backward_is_dense_transpose(oracle, seed, K):
+    nu, ni, u, i = small_graph(seed)
+    Ahat, _ = dense_ahat(nu, ni, u, i)
+    rng = np.random.default_rng(seed)
+    G = rng.standard_normal((nu + ni, 6))
+    direct = [rng.standard_normal((nu + ni, 6)) for _ in range(K - 1)]
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    got = oracle.propagate_bwd(row_ptr, col, G, K, g_layers=direct if K > 1 else None)
+    ref = G
+    for l in range(K - 1, -1, -1):
+        ref = Ahat.T @ ref
+        if l >= 1:
+            ref = ref + direct[l - 1]
+    assert relerr(got, ref) < 1e-12
+
+
+def test_backward_transposes_a_nonsymmetric_structure(oracle):
+    """The scatter form is A^T on any CSR, not only on symmetric ones (every referenced
+    column has a non-empty row, so all weights 1/sqrt(len_i len_j) are finite)."""
+    n = 4
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((n, 3))
+    G = rng.standard_normal((n, 3))
+    row_ptr = np.array([0, 2, 3, 4, 7], dtype=np.int64)
+    col = np.array([1, 3, 0, 3, 0, 1, 2], dtype=np.int32)
+    length = np.diff(row_ptr).astype(np.float64)
+    M = np.zeros((n, n))
+    for r in range(n):
+        for p in range(row_ptr[r], row_ptr[r + 1]):
+            M[r, col[p]] = 1.0 / np.sqrt(length[r] * length[col[p]])
+    assert not np.allclose(M, M.T)
+    assert relerr(oracle.propagate_layer(row_ptr, col, X), M @ X) < 1e-13
+    assert relerr(oracle.propagate_layer_transposed(row_ptr, col, G), M.T @ G) < 1e-13
+
+
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_adjoint_identity(oracle, K):
+    c = make_config(1)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    X = c["X0"].astype(np.float64)
+    G = c["gY"].astype(np.float64)
+    lhs = (oracle.propagate_fwd(row_ptr, col, X, K)[-1] * G).sum()
+    rhs = (X * oracle.propagate_bwd(row_ptr, col, G, K)).sum()
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), 1e-300) + 1e-15 * np.abs(X).sum()
+
+
+def test_backward_finite_differences(oracle):
+    """d/dX of L = 1/2 ||A^^K X||^2 is (A^T)^K (A^^K X)."""
+    nu, ni, u, i = small_graph(51, nu=6, ni=5, ne=14)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    rng = np.random.default_rng(51)
+    X = rng.standard_normal((nu + ni, 2))
+    K = 2
+
+    def loss(Xv):
+        return 0.5 * (oracle.propagate_fwd(row_ptr, col, Xv, K)[-1] ** 2).sum()
+
+    Y = oracle.propagate_fwd(row_ptr, col, X, K)[-1]
+    grad = oracle.propagate_bwd(row_ptr, col, Y, K)
+    h = 1e-6
+    for idx in [(0, 0), (3, 1), (7, 0), (10, 1)]:
+        Xp, Xm = X.copy(), X.copy()
+        Xp[idx] += h
+        Xm[idx] -= h
+        fd = (loss(Xp) - loss(Xm)) / (2 * h)
+        assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(grad[idx]))
+
+
+# ---------------------------------------------------------------- per-node LightGCN update
+def test_no_self_loop_variant_matches_per_node_sums(oracle):
+    """Section 3.1, per-node form: h_u = sum_{i in N(u)} h_i / (sqrt|N(u)| sqrt|N(i)|), and
+    the same with the roles swapped; nodes without neighbours get zero."""
+    nu, ni, u, i = small_graph(61, nu=9, ni=7, ne=20, dup=False)
+    rng = np.random.default_rng(61)
+    H = rng.standard_normal((nu + ni, 3))
+    Nu = {a: sorted(set(int(x) for x in i[u == a])) for a in range(nu)}
+    Ni = {b: sorted(set(int(x) for x in u[i == b])) for b in range(ni)}
+    ref = np.zeros_like(H)
+    for a in range(nu):
+        for b in Nu[a]:
+            ref[a] += H[nu + b] / (np.sqrt(len(Nu[a])) * np.sqrt(len(Ni[b])))
+    for b in range(ni):
+        for a in Ni[b]:
+            ref[nu + b] += H[a] / (np.sqrt(len(Ni[b])) * np.sqrt(len(Nu[a])))
+    row_ptr, col = oracle.build_csr(nu, ni, u, i, add_self_loops=False)
+    assert relerr(oracle.propagate_layer(row_ptr, col, H), ref) < 1e-13
+    Ad, _ = dense_ahat(nu, ni, u, i, self_loops=False)
+    assert relerr(oracle.propagate_layer(row_ptr, col, H), Ad @ H) < 1e-13
+
+
+# ---------------------------------------------------------------- plumbing
+def test_rows_mode_equals_full(oracle):
+    c = make_config(1)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    X = c["X0"].astype(np.float64)
+    full = oracle.propagate_layer(row_ptr, col, X)
+    rows = np.array([0, 5, 1999, 2000, 2999, 17])
+    assert np.array_equal(oracle.propagate_rows(row_ptr, col, X, rows), full[rows])
+
+
+def test_thread_count_does_not_change_bits(oracle):
+    c = make_config(1)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    X = c["X0"].astype(np.float64)
+    nt = oracle.max_threads()
+    oracle.set_threads(1)
+    a = oracle.propagate_layer(row_ptr, col, X)
+    b = oracle.propagate_layer_transposed(row_ptr, col, X)
+    oracle.set_threads(nt)
+    assert np.array_equal(a, oracle.propagate_layer(row_ptr, col, X))
+    assert np.array_equal(b, oracle.propagate_layer_transposed(row_ptr, col, X))
+
+
+def test_bf16_bits_are_read_exactly(oracle):
+    torch = pytest.importorskip("torch")
+    bits = np.arange(0, 65536, 7, dtype=np.uint16)
+    bits = bits[((bits >> 7) & 0xFF) != 0xFF]          # finite values only
+    ref = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    assert np.array_equal(oracle.bf16_bits_to_f64(bits), ref)
+
+
+# ---------------------------------------------------------------- dense update
+@pytest.mark.parametrize("relu", [True, False])
+def test_transform_matches_numpy(oracle, relu):
+    rng = np.random.default_rng(71)
+    P = rng.standard_normal((37, 12))
+    W = rng.standard_normal((12, 9))
+    gH = rng.standard_normal((37, 9))
+    Z, H = oracle.transform_fwd(P, W, relu)
+    assert relerr(Z, P @ W) < 1e-13
+    assert np.array_equal(H, np.maximum(Z, 0) if relu else Z)
+    dP, dW = oracle.transform_bwd(P, W, Z, gH, relu)
+    dZ = gH * (P @ W > 0) if relu else gH
+    assert relerr(dP, dZ @ W.T) < 1e-13
+    assert relerr(dW, P.T @ dZ) < 1e-13
+    dP2, dW2 = oracle.transform_bwd(P, W, H, gH, relu)      # mask from H is the same mask
+    assert np.array_equal(dP, dP2) and np.array_equal(dW, dW2)
+
+
+def test_transform_finite_differences(oracle):
+    rng = np.random.default_rng(72)
+    P = rng.standard_normal((8, 5))
+    W = rng.standard_normal((5, 4))
+    T = rng.standard_normal((8, 4))
+
+    def loss(Pv, Wv):
+        return (oracle.transform_fwd(Pv, Wv, True)[1] * T).sum()
+
+    Z, _ = oracle.transform_fwd(P, W, True)
+    dP, dW = oracle.transform_bwd(P, W, Z, T, True)
+    h = 1e-6
+    for idx in [(0, 0), (3, 2), (7, 4)]:
+        Pp, Pm = P.copy(), P.copy()
+        Pp[idx] += h
+        Pm[idx] -= h
+        assert abs((loss(Pp, W) - loss(Pm, W)) / (2 * h) - dP[idx]) < 1e-6
+    for idx in [(0, 0), (2, 3), (4, 1)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += h
+        Wm[idx] -= h
+        assert abs((loss(P, Wp) - loss(P, Wm)) / (2 * h) - dW[idx]) < 1e-6
