@@ -1,0 +1,155 @@
+/*
+ * e2eg: normalized-adjacency message passing on a user-item interaction graph,
+ * for AMD MI355X (gfx950).  C ABI of libe2eg.so.
+ *
+ * The operator (paper: Section 3, "Notation"): for an undirected graph with adjacency A
+ * (A_ij > 0 iff (i,j) is an edge), A~ = A + I, D~ = D + I with D = diag(A 1), and
+ *     A^ = D~^-1/2 A~ D~^-1/2 .
+ * The path (Section 3.1, LightGCN in matrix form): H(l+1) = A^ H(l), l = 0..K-1, with K equal
+ * to the number of sampled hops (Section 5), and its backward G(l) = A^T G(l+1) (Appendix A,
+ * the "GNN backprop" factor; Section 4.3.2, the J^T dL/dF_gnn terms).  An optional dense
+ * per-layer update H' = relu(P W) follows the generic message-passing layer's update function
+ * psi and the W, sigma of the GraphSAGE layer (Section 3, Section 3.1).
+ *
+ * Conventions for every entry point
+ *   - Nodes: users are 0 .. n_users-1, item i is node n_users + i; n = n_users + n_items.
+ *   - All `d_` pointers are DEVICE pointers, all `h_` pointers HOST pointers.  The caller owns
+ *     every buffer; the library allocates no device memory and keeps no state between calls.
+ *     Inputs are never written.  Scratch memory is passed in as (ws, ws_bytes); the matching
+ *     *_workspace_bytes() query is a pure host function.  Workspace must be 256-byte aligned.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued on it and the
+ *     call returns without waiting, except e2eg_build_csr, which waits once to return nnz.
+ *   - Feature matrices are row-major [n][F] with a leading dimension (in elements) >= F.
+ *     dtype E2EG_F32: float.  dtype E2EG_BF16: bfloat16 bit patterns (uint16); arithmetic is
+ *     fp32 and each stored layer is rounded to nearest-even once.  F must be a multiple of 4
+ *     (fp32) or 8 (bf16), leading dimensions too, and base pointers 16-byte aligned.
+ *   - Return value: E2EG_OK or a negative E2EG_ERR_* code; e2eg_last_error() gives a
+ *     thread-local message for the last failure on the calling thread.  Argument errors are
+ *     found on the host before anything is enqueued.  No C++ exception crosses this boundary.
+ */
+#ifndef E2EG_H
+#define E2EG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define E2EG_OK 0
+#define E2EG_ERR_INVALID_ARG (-1) /* a size, flag, stride or alignment is not acceptable     */
+#define E2EG_ERR_NULL_PTR (-2)    /* a required pointer is NULL                              */
+#define E2EG_ERR_BAD_DTYPE (-3)   /* dtype is not one of E2EG_F32 / E2EG_BF16, or unsupported */
+#define E2EG_ERR_CAPACITY (-4)    /* an output buffer is smaller than the result             */
+#define E2EG_ERR_OVERFLOW (-5)    /* n or nnz would not fit in int32                         */
+#define E2EG_ERR_WORKSPACE (-6)   /* ws is NULL, misaligned or smaller than the query says   */
+#define E2EG_ERR_HIP (-7)         /* a HIP runtime call failed; see e2eg_last_error()        */
+#define E2EG_ERR_BAD_INDEX (-8)   /* an input id is outside its range (found on the device)  */
+
+#define E2EG_F32 0
+#define E2EG_BF16 1
+
+#define E2EG_ADD_SELF_LOOPS 1 /* build_csr flag bit 0: build A~ = A + I (else A itself) */
+
+#define E2EG_TRANSFORM_FWD 0
+#define E2EG_TRANSFORM_BWD 1
+
+const char* e2eg_status_string(int32_t status);
+const char* e2eg_last_error(void);
+int32_t e2eg_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_build_csr: structure of A~ = A + I (Section 3, "Notation") in CSR.
+ *
+ * Input: n_edges pairs (d_user_ids[e], d_item_ids[e]), user ids in [0, n_users), item ids in
+ * [0, n_items), any order, repeats allowed (a repeated pair is one edge: A_ij > 0 iff (i,j) in E).
+ * Each pair gives the two entries (u, n_users+i) and (n_users+i, u).  With E2EG_ADD_SELF_LOOPS
+ * every node also gets its diagonal entry.
+ * Output: d_row_ptr[n+1] (d_row_ptr[0] = 0) and d_col_idx[nnz], columns strictly ascending in
+ * each row; *h_nnz_out = nnz.  col_capacity (entries) must be >= 2*n_edges + n (the bound
+ * without knowing how many pairs repeat); fewer entries may be written.
+ * Errors: OVERFLOW if n or 2*n_edges + n exceeds INT32_MAX; CAPACITY; WORKSPACE; BAD_INDEX if
+ * an id is out of range (outputs are then unspecified).  Waits for the stream once.
+ */
+size_t e2eg_build_csr_workspace_bytes(int32_t n_users, int32_t n_items, int64_t n_edges);
+int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_edges,
+                       const int32_t* d_user_ids, const int32_t* d_item_ids, int32_t flags,
+                       int32_t* d_row_ptr, int32_t* d_col_idx, int64_t col_capacity,
+                       int64_t* h_nnz_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_normalize: D~ and D~^-1/2 (Section 3, "Notation"), plus the launch schedule.
+ *
+ * d_deg[i] = d~_i = sum_j A~_ij = d_row_ptr[i+1] - d_row_ptr[i]  (for a CSR built without
+ * self-loops this is |N(i)|, the count the per-node LightGCN update of Section 3.1 uses);
+ * d_dinv_sqrt[i] = (float)(1 / sqrt((double) d~_i)), and 0 for an empty row.
+ * d_sched (sched_bytes >= e2eg_sched_bytes(n, nnz), 256-byte aligned) receives the row
+ * schedule that e2eg_propagate_* read: rows cut into segments of bounded length so that
+ * power-law rows spread over many wavefronts.  Its content is private to the library and
+ * valid for this (d_row_ptr, n, nnz) only.  d_deg may be NULL.
+ */
+size_t e2eg_sched_bytes(int32_t n, int64_t nnz);
+size_t e2eg_normalize_workspace_bytes(int32_t n, int64_t nnz);
+int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr, int32_t* d_deg,
+                       float* d_dinv_sqrt, void* d_sched, size_t sched_bytes, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_propagate_fwd: H(l+1) = A^ H(l), l = 0..K-1, H(0) = X0 (Section 3.1, matrix form).
+ *
+ * (A^ H)_i = s_i * sum_{j in row i} s_j H_j with s = d_dinv_sqrt; accumulation in fp32.
+ * d_X0 [n][F] (ldx).  d_Xout receives layers 1..K: layer l at d_Xout + (l-1)*layer_stride
+ * elements, each [n][F] with leading dimension ldo.  layer_stride == 0 keeps only H(K) (written
+ * at d_Xout); otherwise layer_stride >= n*ldo.  Every stored layer is written exactly once.
+ * d_Xout must not overlap d_X0.  K >= 1.
+ */
+size_t e2eg_propagate_workspace_bytes(int32_t n, int64_t nnz, int32_t dtype, int32_t F, int32_t K);
+int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                           const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                           const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                           const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
+                           int64_t layer_stride, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_propagate_bwd: the transpose-Jacobian of e2eg_propagate_fwd (Appendix A, "GNN
+ * backprop"; Section 4.3.2, J^T dL/dF_gnn).
+ *
+ * G(K) = d_gXK;  G(l) = A^T G(l+1) + D(l) for l = K-1 .. 0, where D(l) is the optional direct
+ * gradient on layer l (a loss that reads intermediate layers), D(0) = 0; output d_gX0 = G(0).
+ * d_gLayers == NULL means no direct terms; else layer l (1 <= l <= K-1) is at
+ * d_gLayers + (l-1)*g_layer_stride elements with leading dimension ldg.
+ * The CSR must be structurally symmetric (everything e2eg_build_csr produces is), so that
+ * A^T = A^ and the same row schedule serves; this is not checked.
+ */
+int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                           const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                           const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                           const void* d_gXK, int64_t ldg, const void* d_gLayers,
+                           int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_layer_transform: the dense per-layer update (update function psi of the generic
+ * message-passing layer with the W, sigma of the GraphSAGE layer; Section 3, Section 3.1).
+ *
+ * mode E2EG_TRANSFORM_FWD:  Z = P W, H = relu ? max(Z, 0) : Z.
+ *     d_P [n][Fin] (ld Fin), d_W [Fin][Fout] row-major (input x output), d_H [n][Fout] out.
+ *     d_gH, d_gP, d_gW are ignored.
+ * mode E2EG_TRANSFORM_BWD:  dZ = relu ? d_gH * [H > 0] : d_gH;  dP = dZ W^T;  dW = P^T dZ.
+ *     d_H is the forward output (its sign pattern is that of Z); d_gP [n][Fin] out;
+ *     d_gW [Fin][Fout] fp32 out (overwritten, not accumulated).  d_gP or d_gW may be NULL
+ *     to skip that product.
+ * dtype E2EG_BF16 only (bf16 MFMA, fp32 accumulate); Fin and Fout multiples of 32, <= 256.
+ */
+size_t e2eg_layer_transform_workspace_bytes(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
+                                            int32_t dtype);
+int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout, int32_t dtype,
+                             int32_t relu, const void* d_P, const void* d_W, void* d_H,
+                             const void* d_gH, void* d_gP, float* d_gW, void* ws,
+                             size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* E2EG_H */

@@ -1,0 +1,159 @@
+"""ctypes binding of libe2eg.so: same names and argument order as include/e2eg.h.
+
+Pointer arguments accept a torch tensor (its data_ptr() is passed), an int address or None.
+A negative status raises E2egError with the library's message.  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libe2eg.so")
+
+E2EG_OK = 0
+E2EG_ERR_INVALID_ARG = -1
+E2EG_ERR_NULL_PTR = -2
+E2EG_ERR_BAD_DTYPE = -3
+E2EG_ERR_CAPACITY = -4
+E2EG_ERR_OVERFLOW = -5
+E2EG_ERR_WORKSPACE = -6
+E2EG_ERR_HIP = -7
+E2EG_ERR_BAD_INDEX = -8
+E2EG_F32 = 0
+E2EG_BF16 = 1
+E2EG_ADD_SELF_LOOPS = 1
+E2EG_TRANSFORM_FWD = 0
+E2EG_TRANSFORM_BWD = 1
+
+_vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+
+# name -> (restype, argtypes); the list the header declares
+SIGNATURES = {
+    "e2eg_status_string": (ctypes.c_char_p, [_i32]),
+    "e2eg_last_error": (ctypes.c_char_p, []),
+    "e2eg_version": (_i32, []),
+    "e2eg_build_csr_workspace_bytes": (_sz, [_i32, _i32, _i64]),
+    "e2eg_build_csr": (_i32, [_i32, _i32, _i64, _vp, _vp, _i32, _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _sz, _vp]),
+    "e2eg_sched_bytes": (_sz, [_i32, _i64]),
+    "e2eg_normalize_workspace_bytes": (_sz, [_i32, _i64]),
+    "e2eg_normalize": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_propagate_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32, _i32]),
+    "e2eg_propagate_fwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "e2eg_propagate_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
+    "e2eg_layer_transform_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
+    "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+}
+
+_lib = None
+
+
+class E2egError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"e2eg status {status}: {message}")
+        self.status = status
+
+
+def load_library():
+    """Loads libe2eg.so from the package directory.  There is no other implementation: if the
+    library has not been built (paper_2511_20564_amd/build.py) this raises."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_20564_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _check(status: int):
+    if status != E2EG_OK:
+        lib = load_library()
+        raise E2egError(status, f"{lib.e2eg_status_string(status).decode()}: {lib.e2eg_last_error().decode()}")
+
+
+def e2eg_version() -> int:
+    return int(load_library().e2eg_version())
+
+
+def e2eg_status_string(status: int) -> str:
+    return load_library().e2eg_status_string(status).decode()
+
+
+def e2eg_last_error() -> str:
+    return load_library().e2eg_last_error().decode()
+
+
+def e2eg_build_csr_workspace_bytes(n_users, n_items, n_edges) -> int:
+    return int(load_library().e2eg_build_csr_workspace_bytes(n_users, n_items, n_edges))
+
+
+def e2eg_build_csr(n_users, n_items, n_edges, d_user_ids, d_item_ids, flags, d_row_ptr, d_col_idx,
+                   col_capacity, ws, ws_bytes=None, stream=0) -> int:
+    """-> nnz"""
+    nnz = _i64(0)
+    _check(load_library().e2eg_build_csr(n_users, n_items, n_edges, _ptr(d_user_ids), _ptr(d_item_ids), flags,
+                                         _ptr(d_row_ptr), _ptr(d_col_idx), col_capacity, ctypes.byref(nnz),
+                                         _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+    return int(nnz.value)
+
+
+def e2eg_sched_bytes(n, nnz) -> int:
+    return int(load_library().e2eg_sched_bytes(n, nnz))
+
+
+def e2eg_normalize_workspace_bytes(n, nnz) -> int:
+    return int(load_library().e2eg_normalize_workspace_bytes(n, nnz))
+
+
+def e2eg_normalize(n, nnz, d_row_ptr, d_deg, d_dinv_sqrt, d_sched, sched_bytes, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_normalize(n, nnz, _ptr(d_row_ptr), _ptr(d_deg), _ptr(d_dinv_sqrt), _ptr(d_sched),
+                                         _nbytes(d_sched) if sched_bytes is None else sched_bytes, _ptr(ws),
+                                         _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_propagate_workspace_bytes(n, nnz, dtype, F, K) -> int:
+    return int(load_library().e2eg_propagate_workspace_bytes(n, nnz, dtype, F, K))
+
+
+def e2eg_propagate_fwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_X0, ldx, d_Xout, ldo,
+                       layer_stride, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_propagate_fwd(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_dinv_sqrt),
+                                             _ptr(d_sched), dtype, F, K, _ptr(d_X0), ldx, _ptr(d_Xout), ldo,
+                                             layer_stride, _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                             stream or None))
+
+
+def e2eg_propagate_bwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_gXK, ldg, d_gLayers,
+                       g_layer_stride, d_gX0, ldo, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_propagate_bwd(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_dinv_sqrt),
+                                             _ptr(d_sched), dtype, F, K, _ptr(d_gXK), ldg, _ptr(d_gLayers),
+                                             g_layer_stride, _ptr(d_gX0), ldo, _ptr(ws),
+                                             _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype) -> int:
+    return int(load_library().e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype))
+
+
+def e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d_gP, d_gW, ws, ws_bytes=None,
+                         stream=0):
+    _check(load_library().e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, _ptr(d_P), _ptr(d_W), _ptr(d_H),
+                                               _ptr(d_gH), _ptr(d_gP), _ptr(d_gW), _ptr(ws),
+                                               _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))

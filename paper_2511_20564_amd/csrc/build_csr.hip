@@ -1,0 +1,335 @@
+// e2eg_build_csr: (user, item) pairs -> CSR structure of A~ = A + I (paper: Section 3,
+// "Notation"; A_ij > 0 iff (i,j) in E, so repeated pairs are one edge).
+//
+// Design for the GPU: everything is integer work and deterministic.
+//   1. pack each pair into a 64-bit key (user << 32 | item), checking id ranges;
+//   2. LSD radix sort (8-bit digits, only the bits the id ranges use) -> (user, item) order;
+//   3. drop repeats (head flags, prefix sum, compaction) -> E distinct pairs;
+//   4. user rows are read off directly: a user's items are a contiguous, ascending run;
+//   5. swap the key halves and sort stably by item -> (item, user) order gives the item rows;
+//   6. degrees come from run boundaries (no atomics), row_ptr from a prefix sum.
+#include "common.h"
+
+namespace e2eg {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSortItems = 8;
+constexpr int kSortTile = kThreads * kSortItems;  // keys per block
+constexpr int kWaves = kThreads / 64;
+
+inline unsigned blocks_for(int64_t count, int per_block) {
+    return (unsigned)ceil_div(count > 0 ? count : 1, per_block);
+}
+
+__global__ void fill_i32(int32_t* p, int64_t count, int32_t v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+__global__ void pack_pairs(const int32_t* __restrict__ users, const int32_t* __restrict__ items,
+                           int64_t n_edges, int32_t n_users, int32_t n_items,
+                           uint64_t* __restrict__ keys, int32_t* __restrict__ bad) {
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_edges) return;
+    int32_t u = users[e], i = items[e];
+    if (u < 0 || u >= n_users || i < 0 || i >= n_items) {
+        atomicOr(bad, 1);
+        u = 0;
+        i = 0;
+    }
+    keys[e] = ((uint64_t)(uint32_t)u << 32) | (uint32_t)i;
+}
+
+// ---- radix sort, one 8-bit digit per pass --------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __restrict__ keys,
+                                                           int64_t count, int shift,
+                                                           int32_t* __restrict__ hist,
+                                                           int32_t nblocks) {
+    __shared__ int h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t idx = base + k * kThreads + threadIdx.x;
+        if (idx < count) atomicAdd(&h[(int)((keys[idx] >> shift) & 255)], 1);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+}
+
+// Stable scatter.  A block's tile is split into one contiguous chunk per wavefront; a wavefront
+// walks its chunk 64 keys at a time, ranking equal digits by lane order plus a running
+// per-wavefront digit count, so ranks follow input order.
+__global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restrict__ in,
+                                                         uint64_t* __restrict__ out,
+                                                         int64_t count, int shift,
+                                                         const int32_t* __restrict__ offs,
+                                                         int32_t nblocks) {
+    __shared__ int wave_cnt[kWaves][256];
+    for (int k = threadIdx.x; k < kWaves * 256; k += kThreads) (&wave_cnt[0][0])[k] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const int64_t chunk = (int64_t)blockIdx.x * kSortTile + (int64_t)wave * (64 * kSortItems);
+    uint64_t key[kSortItems];
+    int rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const int64_t idx = chunk + r * 64 + lane;
+        const bool valid = idx < count;
+        key[r] = valid ? in[idx] : 0ull;
+        const int d = (int)((key[r] >> shift) & 255);
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (d >> b) & 1;
+            const uint64_t bal = __ballot(valid && bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const int pre = wave_cnt[wave][d];
+        const int below = __popcll(peers & lt_mask);
+        rank[r] = pre + below;
+        if (valid && below == 0) wave_cnt[wave][d] = pre + __popcll(peers);
+    }
+    __syncthreads();
+    {
+        const int d = threadIdx.x;
+        int base = offs[(int64_t)d * nblocks + blockIdx.x];
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            int c = wave_cnt[w][d];
+            wave_cnt[w][d] = base;
+            base += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const int64_t idx = chunk + r * 64 + lane;
+        if (idx < count) {
+            const int d = (int)((key[r] >> shift) & 255);
+            out[(int64_t)wave_cnt[wave][d] + rank[r]] = key[r];
+        }
+    }
+}
+
+__global__ void head_flags(const uint64_t* __restrict__ keys, int64_t count,
+                           int32_t* __restrict__ flags) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) flags[k] = (k == 0 || keys[k] != keys[k - 1]) ? 1 : 0;
+}
+
+__global__ void compact_heads(const uint64_t* __restrict__ keys, int64_t count,
+                              const int32_t* __restrict__ pos, uint64_t* __restrict__ out) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count && (k == 0 || keys[k] != keys[k - 1])) out[pos[k]] = keys[k];
+}
+
+// Keys sorted by their upper half: record where each id's run starts and ends.
+__global__ void run_bounds(const uint64_t* __restrict__ keys, int64_t count,
+                           int32_t* __restrict__ start, int32_t* __restrict__ end) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= count) return;
+    const uint32_t id = (uint32_t)(keys[k] >> 32);
+    if (k == 0 || (uint32_t)(keys[k - 1] >> 32) != id) start[id] = (int32_t)k;
+    if (k == count - 1 || (uint32_t)(keys[k + 1] >> 32) != id) end[id] = (int32_t)(k + 1);
+}
+
+// User rows: pair k of the (user, item)-sorted list lands behind its user's diagonal entry.
+// Also rewrites the key as (item << 32 | user) for the second sort.
+__global__ void fill_user_rows(uint64_t* __restrict__ keys, int64_t count, int32_t n_users,
+                               int32_t self, int32_t* __restrict__ col_idx) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= count) return;
+    const uint64_t key = keys[k];
+    const uint32_t u = (uint32_t)(key >> 32), i = (uint32_t)key;
+    col_idx[k + (int64_t)(u + 1) * self] = n_users + (int32_t)i;
+    keys[k] = ((uint64_t)i << 32) | u;
+}
+
+__global__ void fill_item_rows(const uint64_t* __restrict__ keys, int64_t count, int32_t n_users,
+                               int32_t self, int32_t* __restrict__ col_idx) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= count) return;
+    const uint64_t key = keys[k];
+    const uint32_t i = (uint32_t)(key >> 32), u = (uint32_t)key;
+    col_idx[count + (int64_t)n_users * self + (int64_t)i * self + k] = (int32_t)u;
+}
+
+// counts[v] = run length (+1 with self-loops); counts[n] = 0 so the scan yields row_ptr[n].
+// (in place: `end` becomes the counts)
+__global__ void row_counts(const int32_t* __restrict__ start, int32_t* end, int64_t n,
+                           int32_t self) {
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) end[v] = end[v] - start[v] + self;
+    if (v == n) end[v] = 0;
+}
+
+__global__ void fill_diagonal(const int32_t* __restrict__ row_ptr, int64_t n, int32_t n_users,
+                              int32_t* __restrict__ col_idx) {
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    // user row: itself first (items have larger ids); item row: itself last
+    const int64_t at = v < n_users ? (int64_t)row_ptr[v] : (int64_t)row_ptr[v + 1] - 1;
+    col_idx[at] = (int32_t)v;
+}
+
+int bits_for(int32_t count) {  // bits needed for ids 0 .. count-1
+    int b = 1;
+    while (b < 31 && ((int64_t)1 << b) < count) ++b;
+    return b;
+}
+
+struct BuildWs {
+    uint64_t* buf_a;
+    uint64_t* buf_b;
+    int32_t* pos;
+    int32_t* hist;
+    int32_t* run_start;
+    int32_t* run_end;
+    int32_t* small;  // [0] distinct-pair count, [1] bad-id flag
+    void* scan_ws;
+    size_t bytes;
+};
+
+BuildWs carve_build(void* base, int32_t n_users, int32_t n_items, int64_t n_edges) {
+    const int64_t n = (int64_t)n_users + n_items;
+    const int64_t e = n_edges > 0 ? n_edges : 1;
+    const int64_t nblocks = ceil_div(e, kSortTile);
+    Carver c(base);
+    BuildWs w;
+    w.buf_a = c.take<uint64_t>(e);
+    w.buf_b = c.take<uint64_t>(e);
+    w.pos = c.take<int32_t>(e);
+    w.hist = c.take<int32_t>(256 * nblocks);
+    w.run_start = c.take<int32_t>(n + 1);
+    w.run_end = c.take<int32_t>(n + 1);
+    w.small = c.take<int32_t>(64);
+    int64_t longest = e;
+    if (256 * nblocks > longest) longest = 256 * nblocks;
+    if (n + 1 > longest) longest = n + 1;
+    w.scan_ws = c.take<char>(scan_workspace_bytes(longest));
+    w.bytes = c.size();
+    return w;
+}
+
+// Sorts `count` keys by bits [lo, lo+nbits); result pointer returned through *src (ping-pong).
+int32_t radix_sort(uint64_t** src, uint64_t** dst, int64_t count, int lo, int nbits,
+                   const BuildWs& w, hipStream_t stream) {
+    const int32_t nblocks = (int32_t)ceil_div(count, kSortTile);
+    for (int shift = lo; shift < lo + nbits; shift += 8) {
+        sort_histogram<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, w.hist,
+                                                                       nblocks);
+        E2EG_LAUNCH_CHECK("sort_histogram");
+        E2EG_HIP_TRY(exclusive_scan_i32(w.hist, w.hist, (int64_t)256 * nblocks, nullptr, w.scan_ws,
+                                        stream));
+        sort_scatter<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift,
+                                                                     w.hist, nblocks);
+        E2EG_LAUNCH_CHECK("sort_scatter");
+        uint64_t* t = *src;
+        *src = *dst;
+        *dst = t;
+    }
+    return E2EG_OK;
+}
+
+}  // namespace
+}  // namespace e2eg
+
+using namespace e2eg;
+
+extern "C" size_t e2eg_build_csr_workspace_bytes(int32_t n_users, int32_t n_items,
+                                                 int64_t n_edges) {
+    if (n_users < 0 || n_items < 0 || n_edges < 0) return 0;
+    return carve_build(nullptr, n_users, n_items, n_edges).bytes;
+}
+
+extern "C" int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_edges,
+                                  const int32_t* d_user_ids, const int32_t* d_item_ids,
+                                  int32_t flags, int32_t* d_row_ptr, int32_t* d_col_idx,
+                                  int64_t col_capacity, int64_t* h_nnz_out, void* ws,
+                                  size_t ws_bytes, void* stream_) {
+    if (n_users < 0 || n_items < 0 || n_edges < 0)
+        return fail(E2EG_ERR_INVALID_ARG, "build_csr: negative size");
+    if (flags & ~E2EG_ADD_SELF_LOOPS) return fail(E2EG_ERR_INVALID_ARG, "build_csr: unknown flag bits 0x%x", flags);
+    const int64_t n = (int64_t)n_users + n_items;
+    const int32_t self = (flags & E2EG_ADD_SELF_LOOPS) ? 1 : 0;
+    if (n > INT32_MAX - 1 || n_edges > (int64_t)INT32_MAX || 2 * n_edges + n > (int64_t)INT32_MAX)
+        return fail(E2EG_ERR_OVERFLOW, "build_csr: n=%lld, 2*n_edges+n=%lld exceed int32",
+                    (long long)n, (long long)(2 * n_edges + n));
+    if (!d_row_ptr || !h_nnz_out || (n_edges > 0 && (!d_user_ids || !d_item_ids)))
+        return fail(E2EG_ERR_NULL_PTR, "build_csr: null pointer");
+    if ((2 * n_edges + n * self) > 0 && !d_col_idx)
+        return fail(E2EG_ERR_NULL_PTR, "build_csr: d_col_idx is null");
+    if (col_capacity < 2 * n_edges + n * self)
+        return fail(E2EG_ERR_CAPACITY, "build_csr: col_capacity %lld < 2*n_edges+n = %lld",
+                    (long long)col_capacity, (long long)(2 * n_edges + n * self));
+    if (n_edges > 0 && (n_users == 0 || n_items == 0))
+        return fail(E2EG_ERR_INVALID_ARG, "build_csr: edges given but no users or no items");
+    const size_t need = e2eg_build_csr_workspace_bytes(n_users, n_items, n_edges);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "build_csr: workspace needs %zu bytes, 256-byte aligned", need);
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    BuildWs w = carve_build(ws, n_users, n_items, n_edges);
+    const dim3 blk(kThreads);
+
+    fill_i32<<<dim3(1), dim3(64), 0, stream>>>(w.small, 64, 0);
+    E2EG_LAUNCH_CHECK("fill_i32");
+    fill_i32<<<dim3(blocks_for(n + 1, kThreads)), blk, 0, stream>>>(w.run_start, n + 1, 0);
+    fill_i32<<<dim3(blocks_for(n + 1, kThreads)), blk, 0, stream>>>(w.run_end, n + 1, 0);
+    E2EG_LAUNCH_CHECK("fill_i32");
+
+    uint64_t* src = w.buf_a;
+    uint64_t* dst = w.buf_b;
+    int32_t host_small[2] = {0, 0};
+    if (n_edges > 0) {
+        pack_pairs<<<dim3(blocks_for(n_edges, kThreads)), blk, 0, stream>>>(
+            d_user_ids, d_item_ids, n_edges, n_users, n_items, src, w.small + 1);
+        E2EG_LAUNCH_CHECK("pack_pairs");
+        int32_t st = radix_sort(&src, &dst, n_edges, 0, bits_for(n_items), w, stream);
+        if (st != E2EG_OK) return st;
+        st = radix_sort(&src, &dst, n_edges, 32, bits_for(n_users), w, stream);
+        if (st != E2EG_OK) return st;
+        head_flags<<<dim3(blocks_for(n_edges, kThreads)), blk, 0, stream>>>(src, n_edges, w.pos);
+        E2EG_LAUNCH_CHECK("head_flags");
+        E2EG_HIP_TRY(exclusive_scan_i32(w.pos, w.pos, n_edges, w.small, w.scan_ws, stream));
+        compact_heads<<<dim3(blocks_for(n_edges, kThreads)), blk, 0, stream>>>(src, n_edges, w.pos, dst);
+        E2EG_LAUNCH_CHECK("compact_heads");
+        uint64_t* t = src;
+        src = dst;
+        dst = t;
+        E2EG_HIP_TRY(hipMemcpyAsync(host_small, w.small, sizeof(host_small), hipMemcpyDeviceToHost, stream));
+    }
+    E2EG_HIP_TRY(hipStreamSynchronize(stream));  // the one wait: the pair count sizes what follows
+    if (host_small[1] != 0) return fail(E2EG_ERR_BAD_INDEX, "build_csr: a user or item id is out of range");
+    const int64_t pairs = host_small[0];
+    const int64_t nnz = 2 * pairs + n * self;
+    *h_nnz_out = nnz;
+
+    if (pairs > 0) {
+        const dim3 grid(blocks_for(pairs, kThreads));
+        run_bounds<<<grid, blk, 0, stream>>>(src, pairs, w.run_start, w.run_end);
+        E2EG_LAUNCH_CHECK("run_bounds");
+        fill_user_rows<<<grid, blk, 0, stream>>>(src, pairs, n_users, self, d_col_idx);
+        E2EG_LAUNCH_CHECK("fill_user_rows");
+        int32_t st = radix_sort(&src, &dst, pairs, 32, bits_for(n_items), w, stream);
+        if (st != E2EG_OK) return st;
+        run_bounds<<<grid, blk, 0, stream>>>(src, pairs, w.run_start + n_users, w.run_end + n_users);
+        E2EG_LAUNCH_CHECK("run_bounds");
+        fill_item_rows<<<grid, blk, 0, stream>>>(src, pairs, n_users, self, d_col_idx);
+        E2EG_LAUNCH_CHECK("fill_item_rows");
+    }
+    // row_ptr = exclusive scan of per-row counts
+    row_counts<<<dim3(blocks_for(n + 1, kThreads)), blk, 0, stream>>>(w.run_start, w.run_end, n, self);
+    E2EG_LAUNCH_CHECK("row_counts");
+    E2EG_HIP_TRY(exclusive_scan_i32(w.run_end, d_row_ptr, n + 1, nullptr, w.scan_ws, stream));
+    if (self && n > 0) {
+        fill_diagonal<<<dim3(blocks_for(n, kThreads)), blk, 0, stream>>>(d_row_ptr, n, n_users, d_col_idx);
+        E2EG_LAUNCH_CHECK("fill_diagonal");
+    }
+    return E2EG_OK;
+}

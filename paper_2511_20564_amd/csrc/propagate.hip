@@ -1,0 +1,458 @@
+// e2eg_propagate_fwd / e2eg_propagate_bwd: K layers of H(l+1) = A^ H(l) with
+// A^ = D~^-1/2 (A + I) D~^-1/2 (paper: Section 3 "Notation"; Section 3.1, LightGCN matrix
+// form) and the transposed pass G(l) = A^T G(l+1) (Appendix A, "GNN backprop" factor).
+//
+// How the GPU evaluates it.  With s = d~^-1/2 and Z(l) = S H(l) (rows pre-scaled by s),
+//     H(l+1) = S * (A~ Z(l)),        Z(l+1) = S * H(l+1),
+// so a layer is an UNWEIGHTED sum of neighbour rows of Z followed by one scale per output row:
+// the only per-edge datum read is the 4-byte column index.  Z(0) is made by one streaming
+// pre-scale pass; every later Z(l) is written by the layer that produces it.  Layers the caller
+// asked for are stored as H(l); layers it did not ask for exist only as Z(l).
+//
+// Kernel shape (wave64): a group of G = 16-byte-chunks-per-row lanes reads one neighbour row with
+// 16-byte loads, so a wavefront gathers 64/G neighbour rows per load instruction, several
+// instructions in flight.  Column indices are fetched 64 at a time (one coalesced load) and
+// handed to the groups through cross-lane moves.  Work items are row segments from the
+// schedule; segments of a split row leave fp32 partial sums that a second kernel adds in slot
+// order (in double), so there are no floating-point atomics and results are reproducible.
+#include "common.h"
+
+namespace e2eg {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
+
+// ---- storage types ---------------------------------------------------------------------------
+struct F32 {
+    using elem = float;
+    static constexpr int kVec = 4;  // elements per 16 bytes
+};
+struct BF16 {
+    using elem = uint16_t;
+    static constexpr int kVec = 8;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <typename T>
+__device__ __forceinline__ void load_vec(const typename T::elem* p, float (&v)[T::kVec]);
+
+template <>
+__device__ __forceinline__ void load_vec<F32>(const float* p, float (&v)[4]) {
+    const float4 q = *reinterpret_cast<const float4*>(p);
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<BF16>(const uint16_t* p, float (&v)[8]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+}
+
+template <typename T>
+__device__ __forceinline__ void store_vec(typename T::elem* p, const float (&v)[T::kVec]);
+
+template <>
+__device__ __forceinline__ void store_vec<F32>(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <>
+__device__ __forceinline__ void store_vec<BF16>(uint16_t* p, const float (&v)[8]) {
+    uint4 q;
+    q.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+    q.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+    q.z = f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16);
+    q.w = f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = q;
+}
+
+template <typename T>
+__device__ __forceinline__ float load_one(const typename T::elem* p);
+template <>
+__device__ __forceinline__ float load_one<F32>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_one<BF16>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_one(typename T::elem* p, float v);
+template <>
+__device__ __forceinline__ void store_one<F32>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_one<BF16>(uint16_t* p, float v) { *p = (uint16_t)f32_to_bf16(v); }
+
+// ---- one layer --------------------------------------------------------------------------------
+template <typename T>
+struct LayerArgs {
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const float* dinv_sqrt;
+    SchedView sched;
+    const typename T::elem* zin;  // Z(l) = S H(l), [n][F]
+    int64_t ld_zin;
+    typename T::elem* out_h;      // H(l+1) or null
+    int64_t ld_h;
+    typename T::elem* out_z;      // Z(l+1) = S H(l+1) or null
+    int64_t ld_z;
+    const typename T::elem* addend;  // direct term added to H(l+1) before scaling, or null
+    int64_t ld_add;
+    float* partial;               // [slots][F] fp32
+    int32_t F;
+};
+
+// Per-row finish: h = s * sum (+ addend); store H and/or Z = s * h.
+template <typename T>
+__device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t row, int32_t col,
+                                           float (&acc)[T::kVec]) {
+    const float s = a.dinv_sqrt[row];
+    float h[T::kVec];
+#pragma unroll
+    for (int v = 0; v < T::kVec; ++v) h[v] = s * acc[v];
+    if (a.addend) {
+        float d[T::kVec];
+        load_vec<T>(a.addend + (int64_t)row * a.ld_add + col, d);
+#pragma unroll
+        for (int v = 0; v < T::kVec; ++v) h[v] += d[v];
+    }
+    if (a.out_h) store_vec<T>(a.out_h + (int64_t)row * a.ld_h + col, h);
+    if (a.out_z) {
+#pragma unroll
+        for (int v = 0; v < T::kVec; ++v) h[v] *= s;
+        store_vec<T>(a.out_z + (int64_t)row * a.ld_z + col, h);
+    }
+}
+
+template <typename T, int LOG_G>
+__global__ __launch_bounds__(kThreads) void spmm_segments(const LayerArgs<T> a) {
+    constexpr int G = 1 << LOG_G;   // lanes per neighbour row
+    constexpr int NB = 64 >> LOG_G; // neighbour rows per load instruction
+    constexpr int V = T::kVec;
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (item >= a.sched.header->n_items) return;
+    const int g = lane >> LOG_G;
+    const int c = lane & (G - 1);
+    const int32_t row = a.sched.item_row[item];
+    const int32_t beg = a.sched.item_beg[item];
+    const int32_t slot = a.sched.item_slot[item];
+    const int32_t row_end = a.row_ptr[row + 1];
+    const int32_t end = beg + kSegLen < row_end ? beg + kSegLen : row_end;
+    const int chunks = a.F / V;
+
+    for (int cb = 0; cb < chunks; cb += G) {
+        const int cc = cb + c;
+        const bool active = cc < chunks;
+        const typename T::elem* zcol = a.zin + (active ? cc : 0) * V;
+        float acc[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+
+        for (int32_t base = beg; base < end; base += 64) {
+            const int cnt = end - base < 64 ? end - base : 64;
+            const int32_t idx = lane < cnt ? a.col_idx[base + lane] : -1;
+            int t = 0;
+            for (; t + 4 * NB <= cnt; t += 4 * NB) {  // four independent gathers in flight
+                const int32_t j0 = __shfl(idx, t + g);
+                const int32_t j1 = __shfl(idx, t + NB + g);
+                const int32_t j2 = __shfl(idx, t + 2 * NB + g);
+                const int32_t j3 = __shfl(idx, t + 3 * NB + g);
+                float v0[V], v1[V], v2[V], v3[V];
+                load_vec<T>(zcol + (int64_t)j0 * a.ld_zin, v0);
+                load_vec<T>(zcol + (int64_t)j1 * a.ld_zin, v1);
+                load_vec<T>(zcol + (int64_t)j2 * a.ld_zin, v2);
+                load_vec<T>(zcol + (int64_t)j3 * a.ld_zin, v3);
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += (v0[v] + v1[v]) + (v2[v] + v3[v]);
+            }
+            for (; t < cnt; t += NB) {
+                const int32_t j = __shfl(idx, t + g);
+                if (j >= 0) {
+                    float v0[V];
+                    load_vec<T>(zcol + (int64_t)j * a.ld_zin, v0);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[v] += v0[v];
+                }
+            }
+        }
+        // add the NB group sums together (lanes with equal c)
+#pragma unroll
+        for (int off = G; off < 64; off <<= 1) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[v] += __shfl_xor(acc[v], off);
+        }
+        if (g == 0 && active) {
+            if (slot < 0) {
+                finish_vec<T>(a, row, cc * V, acc);
+            } else {
+                float* p = a.partial + (int64_t)slot * a.F + cc * V;
+#pragma unroll
+                for (int v = 0; v < V; ++v) p[v] = acc[v];
+            }
+        }
+    }
+}
+
+// Rows cut into several segments: add the partial sums in slot order, one thread per column.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void reduce_split_rows(const LayerArgs<T> a) {
+    const int32_t k = blockIdx.x;
+    if (k >= a.sched.header->n_split) return;
+    const int32_t row = a.sched.split_row[k];
+    const int32_t base = a.sched.split_base[k];
+    const int32_t cnt = a.sched.split_cnt[k];
+    const float s = a.dinv_sqrt[row];
+    for (int f = threadIdx.x; f < a.F; f += kThreads) {
+        double sum = 0.0;
+        const float* p = a.partial + (int64_t)base * a.F + f;
+        for (int32_t q = 0; q < cnt; ++q) sum += (double)p[(int64_t)q * a.F];
+        float h = s * (float)sum;
+        if (a.addend) h += load_one<T>(a.addend + (int64_t)row * a.ld_add + f);
+        if (a.out_h) store_one<T>(a.out_h + (int64_t)row * a.ld_h + f, h);
+        if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.ld_z + f, s * h);
+    }
+}
+
+// Z(0) = S X(0): one streaming pass, 16 bytes per thread.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void prescale_rows(const typename T::elem* __restrict__ x,
+                                                          int64_t ldx,
+                                                          const float* __restrict__ dinv_sqrt,
+                                                          typename T::elem* __restrict__ z,
+                                                          int64_t ldz, int64_t n, int32_t F) {
+    constexpr int V = T::kVec;
+    const int chunks = F / V;
+    const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (id >= n * chunks) return;
+    const int64_t row = id / chunks;
+    const int col = (int)(id - row * chunks) * V;
+    float v[V];
+    load_vec<T>(x + row * ldx + col, v);
+    const float s = dinv_sqrt[row];
+#pragma unroll
+    for (int k = 0; k < V; ++k) v[k] *= s;
+    store_vec<T>(z + row * ldz + col, v);
+}
+
+template <typename T>
+int32_t launch_layer(const LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream) {
+    const int chunks = a.F / T::kVec;
+    int log_g = 0;
+    while ((1 << log_g) < chunks && log_g < 6) ++log_g;
+    const int64_t max_items = sched_max_items(n, nnz);
+    const dim3 grid((unsigned)ceil_div(max_items, kWavesPerBlock));
+    const dim3 blk(kThreads);
+    switch (log_g) {
+        case 0: spmm_segments<T, 0><<<grid, blk, 0, stream>>>(a); break;
+        case 1: spmm_segments<T, 1><<<grid, blk, 0, stream>>>(a); break;
+        case 2: spmm_segments<T, 2><<<grid, blk, 0, stream>>>(a); break;
+        case 3: spmm_segments<T, 3><<<grid, blk, 0, stream>>>(a); break;
+        case 4: spmm_segments<T, 4><<<grid, blk, 0, stream>>>(a); break;
+        case 5: spmm_segments<T, 5><<<grid, blk, 0, stream>>>(a); break;
+        default: spmm_segments<T, 6><<<grid, blk, 0, stream>>>(a); break;
+    }
+    E2EG_LAUNCH_CHECK("spmm_segments");
+    if (nnz > kSegLen) {  // otherwise no row can be split
+        reduce_split_rows<T><<<dim3((unsigned)sched_max_split(nnz)), blk, 0, stream>>>(a);
+        E2EG_LAUNCH_CHECK("reduce_split_rows");
+    }
+    return E2EG_OK;
+}
+
+struct PropWs {
+    void* z[2];
+    float* partial;
+    size_t bytes;
+};
+
+PropWs carve_prop(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F, int32_t K) {
+    Carver c(base);
+    PropWs w;
+    const size_t esz = dtype == E2EG_F32 ? 4 : 2;
+    const size_t zbytes = (size_t)(n > 0 ? n : 1) * (size_t)F * esz;
+    w.z[0] = c.take<char>(zbytes);
+    w.z[1] = K > 1 ? c.take<char>(zbytes) : nullptr;
+    w.partial = c.take<float>((size_t)(2 * (nnz / kSegLen) + 2) * (size_t)F);
+    w.bytes = c.size();
+    return w;
+}
+
+int32_t check_common(const char* who, int32_t n, int64_t nnz, const void* row_ptr, const void* col_idx,
+                     const void* dinv, const void* sched, int32_t dtype, int32_t F, int32_t K) {
+    if (n < 0 || nnz < 0) return fail(E2EG_ERR_INVALID_ARG, "%s: negative size", who);
+    if (nnz > (int64_t)INT32_MAX || n == INT32_MAX)
+        return fail(E2EG_ERR_OVERFLOW, "%s: nnz=%lld exceeds int32", who, (long long)nnz);
+    if (dtype != E2EG_F32 && dtype != E2EG_BF16) return fail(E2EG_ERR_BAD_DTYPE, "%s: dtype %d", who, dtype);
+    const int vec = dtype == E2EG_F32 ? 4 : 8;
+    if (F <= 0 || F % vec != 0)
+        return fail(E2EG_ERR_INVALID_ARG, "%s: F=%d must be a positive multiple of %d", who, F, vec);
+    if (K < 1) return fail(E2EG_ERR_INVALID_ARG, "%s: K=%d must be >= 1", who, K);
+    if (!row_ptr || !dinv || !sched || (nnz > 0 && !col_idx))
+        return fail(E2EG_ERR_NULL_PTR, "%s: null graph pointer", who);
+    return E2EG_OK;
+}
+
+int32_t check_matrix(const char* who, const char* name, const void* p, int64_t ld, int32_t F, int32_t dtype) {
+    const int vec = dtype == E2EG_F32 ? 4 : 8;
+    if (!p) return fail(E2EG_ERR_NULL_PTR, "%s: %s is null", who, name);
+    if (!aligned_to(p, 16)) return fail(E2EG_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", who, name);
+    if (ld < F || ld % vec != 0)
+        return fail(E2EG_ERR_INVALID_ARG, "%s: leading dimension of %s (%lld) must be >= F and a multiple of %d",
+                    who, name, (long long)ld, vec);
+    return E2EG_OK;
+}
+
+// Runs K layers.  `in` is the layer-K-side input (X0 for forward, dL/dH(K) for backward);
+// outputs: layer index L = 1..K in forward order.  store(L) says where H of the L-th computed
+// layer goes (null = not kept); add(L) is the direct term added to it (null = none).
+template <typename T>
+int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t* col_idx,
+                   const float* dinv, const void* sched, int32_t F, int32_t K, const void* in,
+                   int64_t ld_in, typename T::elem* const* store, const int64_t* ld_store,
+                   const typename T::elem* const* add, int64_t ld_add, const PropWs& w,
+                   hipStream_t stream) {
+    using E = typename T::elem;
+    SchedView view;
+    sched_carve(const_cast<void*>(sched), n, nnz, &view);
+    const int chunks = F / T::kVec;
+    E* z_cur = static_cast<E*>(w.z[0]);
+    E* z_next = static_cast<E*>(w.z[1]);
+    prescale_rows<T><<<dim3((unsigned)ceil_div((int64_t)n * chunks, kThreads)), dim3(kThreads), 0, stream>>>(
+        static_cast<const E*>(in), ld_in, dinv, z_cur, F, n, F);
+    E2EG_LAUNCH_CHECK("prescale_rows");
+    for (int32_t l = 1; l <= K; ++l) {
+        LayerArgs<T> a;
+        a.row_ptr = row_ptr;
+        a.col_idx = col_idx;
+        a.dinv_sqrt = dinv;
+        a.sched = view;
+        a.zin = z_cur;
+        a.ld_zin = F;
+        a.out_h = store[l - 1];
+        a.ld_h = ld_store[l - 1];
+        a.out_z = l < K ? z_next : nullptr;
+        a.ld_z = F;
+        a.addend = add ? add[l - 1] : nullptr;
+        a.ld_add = ld_add;
+        a.partial = w.partial;
+        a.F = F;
+        int32_t st = launch_layer<T>(a, n, nnz, stream);
+        if (st != E2EG_OK) return st;
+        E* t = z_cur;
+        z_cur = z_next;
+        z_next = t;
+    }
+    return E2EG_OK;
+}
+
+constexpr int kMaxLayers = 64;
+
+}  // namespace
+}  // namespace e2eg
+
+using namespace e2eg;
+
+extern "C" size_t e2eg_propagate_workspace_bytes(int32_t n, int64_t nnz, int32_t dtype, int32_t F,
+                                                 int32_t K) {
+    if (n < 0 || nnz < 0 || F <= 0 || K < 1 || (dtype != E2EG_F32 && dtype != E2EG_BF16)) return 0;
+    return carve_prop(nullptr, n, nnz, dtype, F, K).bytes;
+}
+
+extern "C" int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                      const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
+                                      int64_t layer_stride, void* ws, size_t ws_bytes,
+                                      void* stream_) {
+    const char* who = "propagate_fwd";
+    int32_t st = check_common(who, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K);
+    if (st != E2EG_OK) return st;
+    if (K > kMaxLayers) return fail(E2EG_ERR_INVALID_ARG, "%s: K=%d exceeds %d", who, K, kMaxLayers);
+    if ((st = check_matrix(who, "d_X0", d_X0, ldx, F, dtype)) != E2EG_OK) return st;
+    if ((st = check_matrix(who, "d_Xout", d_Xout, ldo, F, dtype)) != E2EG_OK) return st;
+    const int vec = dtype == E2EG_F32 ? 4 : 8;
+    if (layer_stride != 0 && (layer_stride < (int64_t)n * ldo || layer_stride % vec != 0))
+        return fail(E2EG_ERR_INVALID_ARG, "%s: layer_stride %lld must be 0 or >= n*ldo and a multiple of %d",
+                    who, (long long)layer_stride, vec);
+    const size_t need = e2eg_propagate_workspace_bytes(n, nnz, dtype, F, K);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    if (n == 0) return E2EG_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    PropWs w = carve_prop(ws, n, nnz, dtype, F, K);
+    int64_t lds[kMaxLayers];
+    for (int l = 0; l < K; ++l) lds[l] = ldo;
+    if (dtype == E2EG_F32) {
+        float* store[kMaxLayers];
+        for (int l = 1; l <= K; ++l)
+            store[l - 1] = layer_stride ? static_cast<float*>(d_Xout) + (int64_t)(l - 1) * layer_stride
+                                        : (l == K ? static_cast<float*>(d_Xout) : nullptr);
+        return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
+                               lds, nullptr, 0, w, stream);
+    }
+    uint16_t* store[kMaxLayers];
+    for (int l = 1; l <= K; ++l)
+        store[l - 1] = layer_stride ? static_cast<uint16_t*>(d_Xout) + (int64_t)(l - 1) * layer_stride
+                                    : (l == K ? static_cast<uint16_t*>(d_Xout) : nullptr);
+    return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
+                            lds, nullptr, 0, w, stream);
+}
+
+extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                      const void* d_gXK, int64_t ldg, const void* d_gLayers,
+                                      int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                                      size_t ws_bytes, void* stream_) {
+    const char* who = "propagate_bwd";
+    int32_t st = check_common(who, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K);
+    if (st != E2EG_OK) return st;
+    if (K > kMaxLayers) return fail(E2EG_ERR_INVALID_ARG, "%s: K=%d exceeds %d", who, K, kMaxLayers);
+    if ((st = check_matrix(who, "d_gXK", d_gXK, ldg, F, dtype)) != E2EG_OK) return st;
+    if ((st = check_matrix(who, "d_gX0", d_gX0, ldo, F, dtype)) != E2EG_OK) return st;
+    const int vec = dtype == E2EG_F32 ? 4 : 8;
+    if (d_gLayers && K > 1) {
+        if (!aligned_to(d_gLayers, 16)) return fail(E2EG_ERR_INVALID_ARG, "%s: d_gLayers is not 16-byte aligned", who);
+        if (g_layer_stride < (int64_t)n * ldg || g_layer_stride % vec != 0)
+            return fail(E2EG_ERR_INVALID_ARG, "%s: g_layer_stride %lld must be >= n*ldg and a multiple of %d",
+                        who, (long long)g_layer_stride, vec);
+    }
+    const size_t need = e2eg_propagate_workspace_bytes(n, nnz, dtype, F, K);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    if (n == 0) return E2EG_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    PropWs w = carve_prop(ws, n, nnz, dtype, F, K);
+    int64_t lds[kMaxLayers];
+    for (int l = 0; l < K; ++l) lds[l] = ldo;
+    // Computed layer L (1..K) is G(K-L); its direct term is D(K-L), given for 1 <= K-L <= K-1.
+    if (dtype == E2EG_F32) {
+        float* store[kMaxLayers];
+        const float* add[kMaxLayers];
+        for (int L = 1; L <= K; ++L) {
+            const int l = K - L;
+            store[L - 1] = L == K ? static_cast<float*>(d_gX0) : nullptr;
+            add[L - 1] = (d_gLayers && l >= 1) ? static_cast<const float*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride : nullptr;
+        }
+        return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
+                               lds, add, ldg, w, stream);
+    }
+    uint16_t* store[kMaxLayers];
+    const uint16_t* add[kMaxLayers];
+    for (int L = 1; L <= K; ++L) {
+        const int l = K - L;
+        store[L - 1] = L == K ? static_cast<uint16_t*>(d_gX0) : nullptr;
+        add[L - 1] = (d_gLayers && l >= 1) ? static_cast<const uint16_t*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride : nullptr;
+    }
+    return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
+                            lds, add, ldg, w, stream);
+}

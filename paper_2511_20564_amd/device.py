@@ -1,0 +1,146 @@
+"""Buffer management around the C ABI: torch owns device memory and the stream, libe2eg.so does
+the work.  Nothing here computes; every function sizes buffers, calls one entry point of
+`binding` and hands the tensors back."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("paper_2511_20564_amd needs a GPU: there is no CPU implementation")
+    B.load_library()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _bytes(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return B.E2EG_F32
+    if t.dtype == torch.bfloat16:
+        return B.E2EG_BF16
+    raise TypeError(f"unsupported feature dtype {t.dtype}")
+
+
+@dataclass
+class Graph:
+    """CSR structure of A~ with its degree scaling and launch schedule, all on the device."""
+    n_users: int
+    n_items: int
+    n: int
+    nnz: int
+    row_ptr: torch.Tensor      # int32 [n+1]
+    col_idx: torch.Tensor      # int32 [nnz]
+    deg: torch.Tensor          # int32 [n]
+    dinv_sqrt: torch.Tensor    # float32 [n]
+    sched: torch.Tensor        # uint8, opaque
+
+
+def normalize(n: int, nnz: int, row_ptr: torch.Tensor):
+    """e2eg_normalize on an existing CSR -> (deg, dinv_sqrt, sched)."""
+    _require_gpu()
+    dev = row_ptr.device
+    deg = torch.empty(n, dtype=torch.int32, device=dev)
+    dinv = torch.empty(n, dtype=torch.float32, device=dev)
+    sched = _bytes(B.e2eg_sched_bytes(n, nnz), dev)
+    ws = _bytes(B.e2eg_normalize_workspace_bytes(n, nnz), dev)
+    B.e2eg_normalize(n, nnz, row_ptr, deg, dinv, sched, None, ws, None, _stream())
+    return deg, dinv, sched
+
+
+def build_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Tensor,
+                add_self_loops: bool = True) -> Graph:
+    """e2eg_build_csr followed by e2eg_normalize.  `users`/`items`: int32 device tensors."""
+    _require_gpu()
+    assert users.dtype == torch.int32 and items.dtype == torch.int32 and users.is_cuda and items.is_cuda
+    assert users.is_contiguous() and items.is_contiguous() and users.numel() == items.numel()
+    dev = users.device
+    n = n_users + n_items
+    n_edges = users.numel()
+    flags = B.E2EG_ADD_SELF_LOOPS if add_self_loops else 0
+    cap = 2 * n_edges + n
+    row_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    ws = _bytes(B.e2eg_build_csr_workspace_bytes(n_users, n_items, n_edges), dev)
+    nnz = B.e2eg_build_csr(n_users, n_items, n_edges, users, items, flags, row_ptr, col, cap, ws, None, _stream())
+    del ws
+    col_idx = col[:nnz]
+    deg, dinv, sched = normalize(n, nnz, row_ptr)
+    return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched)
+
+
+def propagate_workspace(g: Graph, dtype: torch.dtype, F: int, K: int) -> torch.Tensor:
+    code = B.E2EG_F32 if dtype == torch.float32 else B.E2EG_BF16
+    return _bytes(B.e2eg_propagate_workspace_bytes(g.n, g.nnz, code, F, K), g.row_ptr.device)
+
+
+def propagate_fwd(g: Graph, X0: torch.Tensor, K: int, all_layers: bool = False, out: torch.Tensor | None = None,
+                  ws: torch.Tensor | None = None) -> torch.Tensor:
+    """H(K) as [n, F], or all of H(1..K) as [K, n, F] when all_layers."""
+    _require_gpu()
+    n, F = X0.shape
+    assert n == g.n and X0.stride(1) == 1
+    if out is None:
+        out = torch.empty((K, n, F) if all_layers else (n, F), dtype=X0.dtype, device=X0.device)
+    if ws is None:
+        ws = propagate_workspace(g, X0.dtype, F, K)
+    B.e2eg_propagate_fwd(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(X0), F, K,
+                         X0, X0.stride(0), out, F, n * F if all_layers else 0, ws, None, _stream())
+    return out
+
+
+def propagate_bwd(g: Graph, gXK: torch.Tensor, K: int, g_layers: torch.Tensor | None = None,
+                  out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """dL/dH(0) from dL/dH(K) (and optional direct terms dL/dH(1..K-1) as [K-1, n, F])."""
+    _require_gpu()
+    n, F = gXK.shape
+    assert n == g.n and gXK.stride(1) == 1
+    if out is None:
+        out = torch.empty((n, F), dtype=gXK.dtype, device=gXK.device)
+    if ws is None:
+        ws = propagate_workspace(g, gXK.dtype, F, K)
+    stride = 0
+    if g_layers is not None:
+        assert g_layers.shape == (K - 1, n, F) and g_layers.is_contiguous() and gXK.stride(0) == F
+        stride = n * F
+    B.e2eg_propagate_bwd(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(gXK), F, K,
+                         gXK, gXK.stride(0), g_layers, stride, out, F, ws, None, _stream())
+    return out
+
+
+def layer_transform_fwd(P: torch.Tensor, W: torch.Tensor, relu: bool = True) -> torch.Tensor:
+    _require_gpu()
+    n, Fin = P.shape
+    Fout = W.shape[1]
+    assert W.shape[0] == Fin and P.is_contiguous() and W.is_contiguous()
+    H = torch.empty((n, Fout), dtype=P.dtype, device=P.device)
+    code = _dtype_code(P)
+    ws = _bytes(B.e2eg_layer_transform_workspace_bytes(B.E2EG_TRANSFORM_FWD, n, Fin, Fout, code), P.device)
+    B.e2eg_layer_transform(B.E2EG_TRANSFORM_FWD, n, Fin, Fout, code, int(relu), P, W, H, None, None, None, ws, None,
+                           _stream())
+    return H
+
+
+def layer_transform_bwd(P: torch.Tensor, W: torch.Tensor, H: torch.Tensor, gH: torch.Tensor, relu: bool = True):
+    """-> (dP [n, Fin] in the storage dtype, dW [Fin, Fout] float32)."""
+    _require_gpu()
+    n, Fin = P.shape
+    Fout = W.shape[1]
+    assert P.is_contiguous() and W.is_contiguous() and H.is_contiguous() and gH.is_contiguous()
+    gP = torch.empty((n, Fin), dtype=P.dtype, device=P.device)
+    gW = torch.empty((Fin, Fout), dtype=torch.float32, device=P.device)
+    code = _dtype_code(P)
+    ws = _bytes(B.e2eg_layer_transform_workspace_bytes(B.E2EG_TRANSFORM_BWD, n, Fin, Fout, code), P.device)
+    B.e2eg_layer_transform(B.E2EG_TRANSFORM_BWD, n, Fin, Fout, code, int(relu), P, W, H, gH, gP, gW, ws, None,
+                           _stream())
+    return gP, gW

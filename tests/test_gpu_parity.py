@@ -1,0 +1,181 @@
+"""GPU parity: libe2eg.so (through its C ABI) against the CPU oracle, same seeded inputs.
+
+Integer results (CSR structure, degrees) must be bit-exact.  Features: max error relative to
+the abs-sum scale <= 1e-5 (fp32) / 2e-2 (bf16 storage, fp32 accumulate).
+"""
+import numpy as np
+import pytest
+import torch
+
+from parity import TOL, assert_close, errors, to_device, to_f64
+from workloads import f32_to_bf16_bits, make_config, make_features, uniform_bipartite
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2511_20564_amd.device as d
+    d.B.load_library()
+    return d
+
+
+def gpu_graph(dev, nu, ni, users, items, self_loops=True):
+    u = torch.from_numpy(np.ascontiguousarray(users, dtype=np.int32)).cuda()
+    i = torch.from_numpy(np.ascontiguousarray(items, dtype=np.int32)).cuda()
+    g = dev.build_graph(nu, ni, u, i, add_self_loops=self_loops)
+    torch.cuda.synchronize()
+    return g
+
+
+def check_structure(oracle, g, nu, ni, users, items, self_loops=True):
+    row_ptr, col = oracle.build_csr(nu, ni, users, items, add_self_loops=self_loops)
+    assert g.nnz == col.size
+    assert np.array_equal(g.row_ptr.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(g.col_idx.cpu().numpy(), col)
+    deg, dinv = oracle.normalize(row_ptr)
+    assert np.array_equal(g.deg.cpu().numpy().astype(np.int64), deg)
+    ref = dinv.astype(np.float32)                     # (float)(1/sqrt((double)d))
+    got = g.dinv_sqrt.cpu().numpy()
+    ulp = np.abs(got.view(np.int32).astype(np.int64) - ref.view(np.int32).astype(np.int64))
+    assert ulp.max(initial=0) <= 1
+    return row_ptr, col
+
+
+# ------------------------------------------------------------------ structure
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (2, 1.0), (3, 0.02)])
+def test_build_csr_configs(dev, oracle, cfg, scale):
+    c = make_config(cfg, scale=scale, features=False)
+    g = gpu_graph(dev, c["n_users"], c["n_items"], c["users"], c["items"])
+    check_structure(oracle, g, c["n_users"], c["n_items"], c["users"], c["items"])
+
+
+@pytest.mark.parametrize("nu,ni,ne", [(1, 1, 1), (1, 1, 0), (5, 3, 0), (7, 300, 2047), (300, 7, 2049),
+                                      (1000, 1, 1000), (1, 1000, 1000), (70000, 66000, 300001)])
+@pytest.mark.parametrize("self_loops", [True, False])
+def test_build_csr_shapes(dev, oracle, nu, ni, ne, self_loops):
+    users, items = uniform_bipartite(nu, ni, ne, seed=nu * 7 + ni)
+    if ne > 10:  # repeated pairs collapse
+        users = np.concatenate([users, users[: ne // 3]])
+        items = np.concatenate([items, items[: ne // 3]])
+    g = gpu_graph(dev, nu, ni, users, items, self_loops)
+    check_structure(oracle, g, nu, ni, users, items, self_loops)
+
+
+def test_build_csr_rejects_bad_ids(dev):
+    u = torch.tensor([0, 5], dtype=torch.int32).cuda()
+    i = torch.tensor([0, 1], dtype=torch.int32).cuda()
+    with pytest.raises(dev.B.E2egError) as e:
+        dev.build_graph(5, 2, u, i)
+    assert e.value.status == dev.B.E2EG_ERR_BAD_INDEX
+
+
+# ------------------------------------------------------------------ propagation
+def run_case(dev, oracle, c, K=None, self_loops=True):
+    K = c["K"] if K is None else K
+    dt = c["dtype"]
+    g = gpu_graph(dev, c["n_users"], c["n_items"], c["users"], c["items"], self_loops)
+    row_ptr, col = check_structure(oracle, g, c["n_users"], c["n_items"], c["users"], c["items"], self_loops)
+    X0 = to_device(c["X0"], dt)
+    gY = to_device(c["gY"], dt)
+    # forward, all layers
+    H = dev.propagate_fwd(g, X0, K, all_layers=True)
+    HK = dev.propagate_fwd(g, X0, K)
+    torch.cuda.synchronize()
+    ref = oracle.propagate_fwd(row_ptr, col, c["X0"], K)
+    scale = oracle.propagate_fwd(row_ptr, col, np.abs(oracle.as_f64(c["X0"])), K)
+    worst = 0.0
+    for k in range(K):
+        comp, _ = assert_close(to_f64(H[k]), ref[k], scale[k], dt, f"fwd layer {k + 1}")
+        worst = max(worst, comp)
+    assert_close(to_f64(HK), ref[K - 1], scale[K - 1], dt, "fwd last layer only")
+    # backward
+    gX0 = dev.propagate_bwd(g, gY, K)
+    torch.cuda.synchronize()
+    refb = oracle.propagate_bwd(row_ptr, col, c["gY"], K)
+    scaleb = oracle.propagate_bwd(row_ptr, col, np.abs(oracle.as_f64(c["gY"])), K)
+    comp, _ = assert_close(to_f64(gX0), refb, scaleb, dt, "bwd")
+    return g, max(worst, comp)
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (2, 1.0), (3, 0.02), (5, 0.002)])
+def test_propagate_configs(dev, oracle, cfg, scale):
+    c = make_config(cfg, scale=scale)
+    _, worst = run_case(dev, oracle, c)
+    print(f"config {cfg} x{scale}: worst componentwise error {worst:.3e} (tol {TOL[c['dtype']]})")
+
+
+@pytest.mark.parametrize("dtype,F", [("f32", 4), ("f32", 24), ("f32", 64), ("f32", 320), ("bf16", 8), ("bf16", 64),
+                                     ("bf16", 200), ("bf16", 1024)])
+@pytest.mark.parametrize("K", [1, 4])
+def test_propagate_feature_widths(dev, oracle, dtype, F, K):
+    nu, ni, ne = 700, 90, 6000        # item rows long enough to be split into segments
+    users, items = uniform_bipartite(nu, ni, ne, seed=F + K)
+    n = nu + ni
+    c = dict(n_users=nu, n_items=ni, users=users, items=items, dtype=dtype, K=K,
+             X0=make_features(n, F, 0.1, 1, dtype), gY=make_features(n, F, 1.0, 2, dtype))
+    run_case(dev, oracle, c)
+
+
+def test_propagate_without_self_loops(dev, oracle):
+    nu, ni, ne = 50, 400, 900         # leaves many items without neighbours
+    users, items = uniform_bipartite(nu, ni, ne, seed=5)
+    n = nu + ni
+    c = dict(n_users=nu, n_items=ni, users=users, items=items, dtype="f32", K=2,
+             X0=make_features(n, 16, 0.1, 1, "f32"), gY=make_features(n, 16, 1.0, 2, "f32"))
+    run_case(dev, oracle, c, self_loops=False)
+
+
+def test_propagate_no_edges_is_identity(dev):
+    n = 37
+    g = gpu_graph(dev, 30, 7, np.zeros(0, np.int32), np.zeros(0, np.int32))
+    X = torch.randn(n, 16, device="cuda")
+    out = dev.propagate_fwd(g, X, 3)
+    torch.cuda.synchronize()
+    assert torch.allclose(out, X, rtol=1e-6, atol=0)
+
+
+def test_propagate_strided_input_and_direct_terms(dev, oracle):
+    c = make_config(1)
+    K = 3
+    g = gpu_graph(dev, c["n_users"], c["n_items"], c["users"], c["items"])
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    n, F = c["n"], c["F"]
+    wide = torch.zeros(n, F + 32, device="cuda")
+    wide[:, :F] = torch.from_numpy(c["X0"]).cuda()
+    out = dev.propagate_fwd(g, wide[:, :F], K)           # leading dimension F + 32
+    ref = oracle.propagate_fwd(row_ptr, col, c["X0"], K)[-1]
+    scale = oracle.propagate_fwd(row_ptr, col, np.abs(c["X0"]).astype(np.float64), K)[-1]
+    assert_close(to_f64(out), ref, scale, "f32", "strided fwd")
+    direct = [make_features(n, F, 1.0, 70 + k, "f32") for k in range(K - 1)]
+    gl = torch.from_numpy(np.stack(direct)).cuda()
+    gY = torch.from_numpy(c["gY"]).cuda()
+    got = dev.propagate_bwd(g, gY, K, g_layers=gl)
+    torch.cuda.synchronize()
+    refb = oracle.propagate_bwd(row_ptr, col, c["gY"], K, g_layers=direct)
+    scaleb = oracle.propagate_bwd(row_ptr, col, np.abs(c["gY"]), K, g_layers=[np.abs(d) for d in direct])
+    assert_close(to_f64(got), refb, scaleb, "f32", "bwd with direct terms")
+
+
+def test_sqrt_degree_is_a_fixed_point_on_gpu(dev):
+    """A^ D~^1/2 1 = D~^1/2 1 at every layer (checked on the GPU's own output)."""
+    c = make_config(2, features=False)
+    g = gpu_graph(dev, c["n_users"], c["n_items"], c["users"], c["items"])
+    v = g.deg.to(torch.float32).sqrt()
+    X = v[:, None].repeat(1, 4).contiguous()
+    out = dev.propagate_fwd(g, X, 3, all_layers=True)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert torch.allclose(out[k], X, rtol=2e-5, atol=0)
+
+
+def test_results_are_reproducible(dev):
+    c = make_config(2)
+    g = gpu_graph(dev, c["n_users"], c["n_items"], c["users"], c["items"])
+    X0 = to_device(c["X0"], "f32")
+    a = dev.propagate_fwd(g, X0, 3).clone()
+    b = dev.propagate_fwd(g, X0, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

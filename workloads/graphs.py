@@ -69,6 +69,9 @@ def uniform_bipartite(n_users: int, n_items: int, n_edges: int, seed: int):
     if n_edges > n_users * n_items:
         raise ValueError("more edges than user-item pairs")
     rng = np.random.default_rng(seed)
+    if 2 * n_edges > n_users * n_items:   # dense: draw the pairs directly
+        keys = rng.choice(n_users * n_items, size=n_edges, replace=False).astype(np.int64)
+        return (keys // n_items).astype(np.int32), (keys % n_items).astype(np.int32)
     keys = np.empty(0, dtype=np.int64)
     while keys.size < n_edges:
         extra = rng.integers(0, n_users * n_items, size=n_edges - keys.size, dtype=np.int64)
