@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One step = K-layer normalized propagation forward plus backward (2K neighbour-sum passes) on the
+resident graph of the 50 M-edge power-law workload (bf16, F=128, K=3).  Graph construction
+(e2eg_build_csr + e2eg_normalize) happens once per graph and is timed separately.
+Prints ONE JSON line on stdout (progress goes to stderr).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload index (3 = headline)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (experiments only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    os.environ.setdefault("E2EG_WORKLOAD_CACHE", "/tmp/e2eg_workload_cache")
+    import numpy as np
+    import torch
+
+    import paper_2511_20564_amd.device as dev
+    from paper_2511_20564_amd import binding as B
+    from workloads import make_config
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    B.load_library()
+
+    t0 = time.time()
+    c = make_config(args.config, scale=args.scale)
+    log(f"[bench] workload {c['name']} generated in {time.time() - t0:.1f}s: n={c['n']} E={c['n_edges']}")
+    K, F, dt = c["K"], c["F"], c["dtype"]
+    esz = 2 if dt == "bf16" else 4
+
+    def dev_features(a):
+        if dt == "bf16":
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    users = torch.from_numpy(c["users"]).cuda()
+    items = torch.from_numpy(c["items"]).cuda()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    g = dev.build_graph(c["n_users"], c["n_items"], users, items)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t1) * 1e3
+    t1 = time.perf_counter()
+    g.deg, g.dinv_sqrt, g.sched = dev.normalize(g.n, g.nnz, g.row_ptr, g.col_idx)
+    torch.cuda.synchronize()
+    normalize_ms = (time.perf_counter() - t1) * 1e3
+    del users, items
+    n, nnz = g.n, g.nnz
+    log(f"[bench] graph on device: nnz={nnz}, build_csr+normalize {build_ms:.1f} ms, normalize alone {normalize_ms:.2f} ms")
+
+    X0 = dev_features(c["X0"])
+    gY = dev_features(c["gY"])
+    out_f = torch.empty_like(X0)
+    out_b = torch.empty_like(X0)
+    ws = dev.propagate_workspace(g, X0.dtype, F, K)
+
+    def step():
+        dev.propagate_fwd(g, X0, K, out=out_f, ws=ws)
+        dev.propagate_bwd(g, gY, K, out=out_b, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.e2eg_profile_begin(2 * K * args.steps)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    kernel_ms = B.e2eg_profile_end(2 * K * args.steps)
+    ms_per_step = elapsed / args.steps * 1e3
+    gteps = nnz * K * 2 / (ms_per_step * 1e-3) / 1e9
+    log(f"[bench] {ms_per_step:.3f} ms/step, {gteps:.2f} GTEPS")
+
+    # forward and backward alone (information only)
+    def timed(fn, reps=5):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps * 1e3
+
+    fwd_ms = timed(lambda: dev.propagate_fwd(g, X0, K, out=out_f, ws=ws))
+    bwd_ms = timed(lambda: dev.propagate_bwd(g, gY, K, out=out_b, ws=ws))
+
+    # roofline of the neighbour-sum kernel: algorithmic bytes of one layer over its mean duration
+    alg_bytes = 4 * nnz + 4 * (n + 1) + 4 * n + 2 * n * F * esz
+    gather_bytes = alg_bytes - n * F * esz + nnz * F * esz + 4 * nnz
+    avg_kernel_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
+    achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "spmm_rows", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "alg_bytes_per_launch": alg_bytes, "avg_kernel_ms": round(avg_kernel_ms, 4),
+        "launches_timed": len(kernel_ms),
+        "gather_GBs": round(gather_bytes / (avg_kernel_ms * 1e-3) / 1e9, 1),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t1 = time.time()
+        row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+        log(f"[bench] oracle CSR built in {time.time() - t1:.1f}s")
+        Xd = oracle.as_f64(c["X0"])
+        t1 = time.perf_counter()
+        Y = oracle.propagate_layer(row_ptr, col, Xd)
+        t_f = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        oracle.propagate_layer_transposed(row_ptr, col, Y)
+        t_b = time.perf_counter() - t1
+        cpu = {
+            "value": round(2 * col.size / (t_f + t_b) / 1e9, 4), "unit": "GTEPS", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"one forward layer ({t_f:.1f}s) + one transposed layer ({t_b:.1f}s) of the same graph, "
+                      f"fp64, all F={F} columns",
+        }
+        log(f"[bench] oracle: {cpu['value']} GTEPS on {cpu['cores']} threads")
+
+    line = {
+        "metric": "normalized-SpMM GTEPS (edges*layers/s) fwd+bwd", "value": round(gteps, 3), "unit": "GTEPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config} ({c['name']}): {c['n_users']} users + {c['n_items']} items, "
+                        f"{c['n_edges']} edges, power-law, symmetrized + self-loops, {dt} F={F}, K={K} fwd+bwd",
+            "scale": args.scale, "seed": c["seed"], "n": n, "nnz": nnz, "max_degree": int(g.deg.max().item()),
+            "F": F, "K": K,
+        },
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+        "build_csr_ms": round(build_ms - normalize_ms, 3), "normalize_ms": round(normalize_ms, 3),
+        "alg_GBs": round(alg_bytes * 2 * K / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

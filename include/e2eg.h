@@ -86,14 +86,15 @@ int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_edges,
  * d_dinv_sqrt[i] = (float)(1 / sqrt((double) d~_i)), and 0 for an empty row.
  * d_sched (sched_bytes >= e2eg_sched_bytes(n, nnz), 256-byte aligned) receives the row
  * schedule that e2eg_propagate_* read: rows cut into segments of bounded length so that
- * power-law rows spread over many wavefronts.  Its content is private to the library and
- * valid for this (d_row_ptr, n, nnz) only.  d_deg may be NULL.
+ * power-law rows spread over many wavefronts, the segments ordered by their first column
+ * (d_col_idx is read for that).  Its content is private to the library and valid for this
+ * (d_row_ptr, d_col_idx, n, nnz) only.  d_deg may be NULL.
  */
 size_t e2eg_sched_bytes(int32_t n, int64_t nnz);
 size_t e2eg_normalize_workspace_bytes(int32_t n, int64_t nnz);
-int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr, int32_t* d_deg,
-                       float* d_dinv_sqrt, void* d_sched, size_t sched_bytes, void* ws,
-                       size_t ws_bytes, void* stream);
+int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                       const int32_t* d_col_idx, int32_t* d_deg, float* d_dinv_sqrt,
+                       void* d_sched, size_t sched_bytes, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * e2eg_propagate_fwd: H(l+1) = A^ H(l), l = 0..K-1, H(0) = X0 (Section 3.1, matrix form).
@@ -148,6 +149,18 @@ int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
                              int32_t relu, const void* d_P, const void* d_W, void* d_H,
                              const void* d_gH, void* d_gP, float* d_gW, void* ws,
                              size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the path): per-launch duration of the neighbour-sum kernel, the
+ * kernel that moves nearly all bytes of e2eg_propagate_*.  Between e2eg_profile_begin() and
+ * e2eg_profile_end() every launch of that kernel made by the calling thread is bracketed by a
+ * pair of HIP events on its own stream (up to `capacity` launches; later ones are not timed).
+ * e2eg_profile_end() waits for the recorded events, writes up to h_capacity durations in
+ * milliseconds (launch order) to h_ms, stores the number recorded in *h_count and switches
+ * recording off.  Uses host memory and HIP events only.
+ */
+int32_t e2eg_profile_begin(int32_t capacity);
+int32_t e2eg_profile_end(float* h_ms, int32_t h_capacity, int32_t* h_count);
 
 #ifdef __cplusplus
 }

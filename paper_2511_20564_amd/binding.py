@@ -37,12 +37,14 @@ SIGNATURES = {
     "e2eg_build_csr": (_i32, [_i32, _i32, _i64, _vp, _vp, _i32, _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _sz, _vp]),
     "e2eg_sched_bytes": (_sz, [_i32, _i64]),
     "e2eg_normalize_workspace_bytes": (_sz, [_i32, _i64]),
-    "e2eg_normalize": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_normalize": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
     "e2eg_propagate_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32, _i32]),
     "e2eg_propagate_fwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "e2eg_propagate_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_layer_transform_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "e2eg_profile_begin": (_i32, [_i32]),
+    "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
 }
 
 _lib = None
@@ -122,8 +124,10 @@ def e2eg_normalize_workspace_bytes(n, nnz) -> int:
     return int(load_library().e2eg_normalize_workspace_bytes(n, nnz))
 
 
-def e2eg_normalize(n, nnz, d_row_ptr, d_deg, d_dinv_sqrt, d_sched, sched_bytes, ws, ws_bytes=None, stream=0):
-    _check(load_library().e2eg_normalize(n, nnz, _ptr(d_row_ptr), _ptr(d_deg), _ptr(d_dinv_sqrt), _ptr(d_sched),
+def e2eg_normalize(n, nnz, d_row_ptr, d_col_idx, d_deg, d_dinv_sqrt, d_sched, sched_bytes, ws, ws_bytes=None,
+                   stream=0):
+    _check(load_library().e2eg_normalize(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_deg), _ptr(d_dinv_sqrt),
+                                         _ptr(d_sched),
                                          _nbytes(d_sched) if sched_bytes is None else sched_bytes, _ptr(ws),
                                          _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
 
@@ -157,3 +161,15 @@ def e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d
     _check(load_library().e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, _ptr(d_P), _ptr(d_W), _ptr(d_H),
                                                _ptr(d_gH), _ptr(d_gP), _ptr(d_gW), _ptr(ws),
                                                _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_profile_begin(capacity: int):
+    _check(load_library().e2eg_profile_begin(capacity))
+
+
+def e2eg_profile_end(capacity: int):
+    """-> list of per-launch durations in ms"""
+    buf = (ctypes.c_float * max(capacity, 1))()
+    count = _i32(0)
+    _check(load_library().e2eg_profile_end(buf, capacity, ctypes.byref(count)))
+    return [float(buf[k]) for k in range(min(capacity, count.value))]

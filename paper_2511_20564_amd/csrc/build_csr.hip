@@ -14,9 +14,6 @@ namespace e2eg {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSortItems = 8;
-constexpr int kSortTile = kThreads * kSortItems;  // keys per block
-constexpr int kWaves = kThreads / 64;
 
 inline unsigned blocks_for(int64_t count, int per_block) {
     return (unsigned)ceil_div(count > 0 ? count : 1, per_block);
@@ -39,81 +36,6 @@ __global__ void pack_pairs(const int32_t* __restrict__ users, const int32_t* __r
         i = 0;
     }
     keys[e] = ((uint64_t)(uint32_t)u << 32) | (uint32_t)i;
-}
-
-// ---- radix sort, one 8-bit digit per pass --------------------------------------------------
-__global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __restrict__ keys,
-                                                           int64_t count, int shift,
-                                                           int32_t* __restrict__ hist,
-                                                           int32_t nblocks) {
-    __shared__ int h[256];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
-#pragma unroll
-    for (int k = 0; k < kSortItems; ++k) {
-        int64_t idx = base + k * kThreads + threadIdx.x;
-        if (idx < count) atomicAdd(&h[(int)((keys[idx] >> shift) & 255)], 1);
-    }
-    __syncthreads();
-    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
-}
-
-// Stable scatter.  A block's tile is split into one contiguous chunk per wavefront; a wavefront
-// walks its chunk 64 keys at a time, ranking equal digits by lane order plus a running
-// per-wavefront digit count, so ranks follow input order.
-__global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restrict__ in,
-                                                         uint64_t* __restrict__ out,
-                                                         int64_t count, int shift,
-                                                         const int32_t* __restrict__ offs,
-                                                         int32_t nblocks) {
-    __shared__ int wave_cnt[kWaves][256];
-    for (int k = threadIdx.x; k < kWaves * 256; k += kThreads) (&wave_cnt[0][0])[k] = 0;
-    __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const int64_t chunk = (int64_t)blockIdx.x * kSortTile + (int64_t)wave * (64 * kSortItems);
-    uint64_t key[kSortItems];
-    int rank[kSortItems];
-#pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
-        const int64_t idx = chunk + r * 64 + lane;
-        const bool valid = idx < count;
-        key[r] = valid ? in[idx] : 0ull;
-        const int d = (int)((key[r] >> shift) & 255);
-        uint64_t peers = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const bool bit = (d >> b) & 1;
-            const uint64_t bal = __ballot(valid && bit);
-            peers &= bit ? bal : ~bal;
-        }
-        const int pre = wave_cnt[wave][d];
-        const int below = __popcll(peers & lt_mask);
-        rank[r] = pre + below;
-        if (valid && below == 0) wave_cnt[wave][d] = pre + __popcll(peers);
-    }
-    __syncthreads();
-    {
-        const int d = threadIdx.x;
-        int base = offs[(int64_t)d * nblocks + blockIdx.x];
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            int c = wave_cnt[w][d];
-            wave_cnt[w][d] = base;
-            base += c;
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
-        const int64_t idx = chunk + r * 64 + lane;
-        if (idx < count) {
-            const int d = (int)((key[r] >> shift) & 255);
-            out[(int64_t)wave_cnt[wave][d] + rank[r]] = key[r];
-        }
-    }
 }
 
 __global__ void head_flags(const uint64_t* __restrict__ keys, int64_t count,
@@ -177,17 +99,11 @@ __global__ void fill_diagonal(const int32_t* __restrict__ row_ptr, int64_t n, in
     col_idx[at] = (int32_t)v;
 }
 
-int bits_for(int32_t count) {  // bits needed for ids 0 .. count-1
-    int b = 1;
-    while (b < 31 && ((int64_t)1 << b) < count) ++b;
-    return b;
-}
-
 struct BuildWs {
     uint64_t* buf_a;
     uint64_t* buf_b;
     int32_t* pos;
-    int32_t* hist;
+    void* sort_ws;
     int32_t* run_start;
     int32_t* run_end;
     int32_t* small;  // [0] distinct-pair count, [1] bad-id flag
@@ -198,42 +114,20 @@ struct BuildWs {
 BuildWs carve_build(void* base, int32_t n_users, int32_t n_items, int64_t n_edges) {
     const int64_t n = (int64_t)n_users + n_items;
     const int64_t e = n_edges > 0 ? n_edges : 1;
-    const int64_t nblocks = ceil_div(e, kSortTile);
     Carver c(base);
     BuildWs w;
     w.buf_a = c.take<uint64_t>(e);
     w.buf_b = c.take<uint64_t>(e);
     w.pos = c.take<int32_t>(e);
-    w.hist = c.take<int32_t>(256 * nblocks);
+    w.sort_ws = c.take<char>(radix_sort_workspace_bytes(e));
     w.run_start = c.take<int32_t>(n + 1);
     w.run_end = c.take<int32_t>(n + 1);
     w.small = c.take<int32_t>(64);
     int64_t longest = e;
-    if (256 * nblocks > longest) longest = 256 * nblocks;
     if (n + 1 > longest) longest = n + 1;
     w.scan_ws = c.take<char>(scan_workspace_bytes(longest));
     w.bytes = c.size();
     return w;
-}
-
-// Sorts `count` keys by bits [lo, lo+nbits); result pointer returned through *src (ping-pong).
-int32_t radix_sort(uint64_t** src, uint64_t** dst, int64_t count, int lo, int nbits,
-                   const BuildWs& w, hipStream_t stream) {
-    const int32_t nblocks = (int32_t)ceil_div(count, kSortTile);
-    for (int shift = lo; shift < lo + nbits; shift += 8) {
-        sort_histogram<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, w.hist,
-                                                                       nblocks);
-        E2EG_LAUNCH_CHECK("sort_histogram");
-        E2EG_HIP_TRY(exclusive_scan_i32(w.hist, w.hist, (int64_t)256 * nblocks, nullptr, w.scan_ws,
-                                        stream));
-        sort_scatter<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift,
-                                                                     w.hist, nblocks);
-        E2EG_LAUNCH_CHECK("sort_scatter");
-        uint64_t* t = *src;
-        *src = *dst;
-        *dst = t;
-    }
-    return E2EG_OK;
 }
 
 }  // namespace
@@ -290,9 +184,9 @@ extern "C" int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_ed
         pack_pairs<<<dim3(blocks_for(n_edges, kThreads)), blk, 0, stream>>>(
             d_user_ids, d_item_ids, n_edges, n_users, n_items, src, w.small + 1);
         E2EG_LAUNCH_CHECK("pack_pairs");
-        int32_t st = radix_sort(&src, &dst, n_edges, 0, bits_for(n_items), w, stream);
+        int32_t st = radix_sort_u64(&src, &dst, n_edges, 0, bits_for(n_items), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
-        st = radix_sort(&src, &dst, n_edges, 32, bits_for(n_users), w, stream);
+        st = radix_sort_u64(&src, &dst, n_edges, 32, bits_for(n_users), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
         head_flags<<<dim3(blocks_for(n_edges, kThreads)), blk, 0, stream>>>(src, n_edges, w.pos);
         E2EG_LAUNCH_CHECK("head_flags");
@@ -316,7 +210,7 @@ extern "C" int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_ed
         E2EG_LAUNCH_CHECK("run_bounds");
         fill_user_rows<<<grid, blk, 0, stream>>>(src, pairs, n_users, self, d_col_idx);
         E2EG_LAUNCH_CHECK("fill_user_rows");
-        int32_t st = radix_sort(&src, &dst, pairs, 32, bits_for(n_items), w, stream);
+        int32_t st = radix_sort_u64(&src, &dst, pairs, 32, bits_for(n_items), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
         run_bounds<<<grid, blk, 0, stream>>>(src, pairs, w.run_start + n_users, w.run_end + n_users);
         E2EG_LAUNCH_CHECK("run_bounds");

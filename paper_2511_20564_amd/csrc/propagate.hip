@@ -12,16 +12,17 @@
 // Kernel shape (wave64): a group of G = 16-byte-chunks-per-row lanes reads one neighbour row with
 // 16-byte loads, so a wavefront gathers 64/G neighbour rows per load instruction, several
 // instructions in flight.  Column indices are fetched 64 at a time (one coalesced load) and
-// handed to the groups through cross-lane moves.  Work items are row segments from the
-// schedule; segments of a split row leave fp32 partial sums that a second kernel adds in slot
-// order (in double), so there are no floating-point atomics and results are reproducible.
+// handed to the groups through cross-lane moves, the next 64 requested before the current
+// gathers are consumed.  Work items come from the schedule: whole short rows (several per
+// wavefront) and segments of long rows; segments leave fp32 partial sums that a second kernel
+// adds in a fixed order (in double), so there are no floating-point atomics and results are
+// reproducible.
 #include "common.h"
 
 namespace e2eg {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kThreads = 64 * kWavesPerBlock;
 
 // ---- storage types ---------------------------------------------------------------------------
 struct F32 {
@@ -106,7 +107,24 @@ struct LayerArgs {
     int64_t ld_add;
     float* partial;               // [slots][F] fp32
     int32_t F;
+    int32_t seg_blocks;           // workgroups that walk seg_items; the rest walk short_items
 };
+
+// 16 raw bytes of a feature row -> added into fp32 accumulators.
+template <typename T>
+__device__ __forceinline__ void accumulate(float (&acc)[T::kVec], const uint4 q);
+template <>
+__device__ __forceinline__ void accumulate<F32>(float (&acc)[4], const uint4 q) {
+    acc[0] += __uint_as_float(q.x); acc[1] += __uint_as_float(q.y);
+    acc[2] += __uint_as_float(q.z); acc[3] += __uint_as_float(q.w);
+}
+template <>
+__device__ __forceinline__ void accumulate<BF16>(float (&acc)[8], const uint4 q) {
+    acc[0] += __uint_as_float(q.x << 16); acc[1] += __uint_as_float(q.x & 0xffff0000u);
+    acc[2] += __uint_as_float(q.y << 16); acc[3] += __uint_as_float(q.y & 0xffff0000u);
+    acc[4] += __uint_as_float(q.z << 16); acc[5] += __uint_as_float(q.z & 0xffff0000u);
+    acc[6] += __uint_as_float(q.w << 16); acc[7] += __uint_as_float(q.w & 0xffff0000u);
+}
 
 // Per-row finish: h = s * sum (+ addend); store H and/or Z = s * h.
 template <typename T>
@@ -130,21 +148,23 @@ __device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t row, i
     }
 }
 
+// First (up to) 64 column indices of a work item, one per lane; -1 beyond its end.
+__device__ __forceinline__ int32_t first_indices(const int32_t* __restrict__ col_idx, const WorkItem& w,
+                                                 int lane) {
+    return (w.row >= 0 && lane < w.end - w.beg) ? col_idx[w.beg + lane] : -1;
+}
+
+// Sums the neighbour rows of one work item and stores the row (or its partial sum).
+// `idx_first` holds the item's first 64 column indices, fetched ahead by the caller.
 template <typename T, int LOG_G>
-__global__ __launch_bounds__(kThreads) void spmm_segments(const LayerArgs<T> a) {
-    constexpr int G = 1 << LOG_G;   // lanes per neighbour row
-    constexpr int NB = 64 >> LOG_G; // neighbour rows per load instruction
+__device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w, const int32_t idx_first,
+                                         const int lane) {
+    constexpr int G = 1 << LOG_G;    // lanes per neighbour row
+    constexpr int NB = 64 >> LOG_G;  // neighbour rows per load instruction
     constexpr int V = T::kVec;
-    const int lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (item >= a.sched.header->n_items) return;
+    constexpr int U = 8;             // independent gathers in flight per lane
     const int g = lane >> LOG_G;
     const int c = lane & (G - 1);
-    const int32_t row = a.sched.item_row[item];
-    const int32_t beg = a.sched.item_beg[item];
-    const int32_t slot = a.sched.item_slot[item];
-    const int32_t row_end = a.row_ptr[row + 1];
-    const int32_t end = beg + kSegLen < row_end ? beg + kSegLen : row_end;
     const int chunks = a.F / V;
 
     for (int cb = 0; cb < chunks; cb += G) {
@@ -155,32 +175,25 @@ __global__ __launch_bounds__(kThreads) void spmm_segments(const LayerArgs<T> a) 
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[v] = 0.0f;
 
-        for (int32_t base = beg; base < end; base += 64) {
-            const int cnt = end - base < 64 ? end - base : 64;
-            const int32_t idx = lane < cnt ? a.col_idx[base + lane] : -1;
-            int t = 0;
-            for (; t + 4 * NB <= cnt; t += 4 * NB) {  // four independent gathers in flight
-                const int32_t j0 = __shfl(idx, t + g);
-                const int32_t j1 = __shfl(idx, t + NB + g);
-                const int32_t j2 = __shfl(idx, t + 2 * NB + g);
-                const int32_t j3 = __shfl(idx, t + 3 * NB + g);
-                float v0[V], v1[V], v2[V], v3[V];
-                load_vec<T>(zcol + (int64_t)j0 * a.ld_zin, v0);
-                load_vec<T>(zcol + (int64_t)j1 * a.ld_zin, v1);
-                load_vec<T>(zcol + (int64_t)j2 * a.ld_zin, v2);
-                load_vec<T>(zcol + (int64_t)j3 * a.ld_zin, v3);
+        int32_t idx = idx_first;
+        for (int32_t base = w.beg; base < w.end; base += 64) {
+            const int cnt = w.end - base < 64 ? w.end - base : 64;
+            int32_t idx_next = -1;  // next 64 indices, requested before this block's gathers
+            if (base + 64 < w.end && lane < w.end - base - 64) idx_next = a.col_idx[base + 64 + lane];
+            for (int t = 0; t < cnt; t += U * NB) {
+                uint4 q[U];
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += (v0[v] + v1[v]) + (v2[v] + v3[v]);
-            }
-            for (; t < cnt; t += NB) {
-                const int32_t j = __shfl(idx, t + g);
-                if (j >= 0) {
-                    float v0[V];
-                    load_vec<T>(zcol + (int64_t)j * a.ld_zin, v0);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) acc[v] += v0[v];
+                for (int u = 0; u < U; ++u) {
+                    const int src = t + u * NB + g;
+                    const int32_t j = __shfl(idx, src & 63);
+                    q[u] = make_uint4(0u, 0u, 0u, 0u);
+                    if (src < cnt && j >= 0)
+                        q[u] = *reinterpret_cast<const uint4*>(zcol + (int64_t)j * a.ld_zin);
                 }
+#pragma unroll
+                for (int u = 0; u < U; ++u) accumulate<T>(acc, q[u]);
             }
+            idx = idx_next;
         }
         // add the NB group sums together (lanes with equal c)
 #pragma unroll
@@ -189,34 +202,103 @@ __global__ __launch_bounds__(kThreads) void spmm_segments(const LayerArgs<T> a) 
             for (int v = 0; v < V; ++v) acc[v] += __shfl_xor(acc[v], off);
         }
         if (g == 0 && active) {
-            if (slot < 0) {
-                finish_vec<T>(a, row, cc * V, acc);
+            if (w.slot < 0) {
+                finish_vec<T>(a, w.row, cc * V, acc);
             } else {
-                float* p = a.partial + (int64_t)slot * a.F + cc * V;
+                float* p = a.partial + (int64_t)w.slot * a.F + cc * V;
 #pragma unroll
-                for (int v = 0; v < V; ++v) p[v] = acc[v];
+                for (int v = 0; v < V; v += 4)
+                    *reinterpret_cast<float4*>(p + v) = make_float4(acc[v], acc[v + 1], acc[v + 2], acc[v + 3]);
             }
         }
     }
 }
 
-// Rows cut into several segments: add the partial sums in slot order, one thread per column.
+// Workgroups [0, seg_blocks): one segment of a long row per wavefront (placed per XCD by the
+// schedule).  Workgroups beyond: kShortPerWave whole rows per wavefront, the next row's column
+// indices requested while the current row's gathers are in flight.
+template <typename T, int LOG_G>
+__global__ __launch_bounds__(kThreads) void spmm_rows(const LayerArgs<T> a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if ((int32_t)blockIdx.x < a.seg_blocks) {
+        const WorkItem w = a.sched.seg_items[(int64_t)blockIdx.x * kWavesPerBlock + wave];
+        if (w.row < 0) return;
+        run_item<T, LOG_G>(a, w, first_indices(a.col_idx, w, lane), lane);
+        return;
+    }
+    const int64_t first = (((int64_t)blockIdx.x - a.seg_blocks) * kWavesPerBlock + wave) * kShortPerWave;
+    const int32_t n_short = a.sched.header->n_short;
+    if (first >= n_short) return;
+    WorkItem w[kShortPerWave];
+#pragma unroll
+    for (int r = 0; r < kShortPerWave; ++r)
+        w[r] = first + r < n_short ? a.sched.short_items[first + r] : WorkItem{-1, 0, 0, -1};
+    int32_t idx_cur = first_indices(a.col_idx, w[0], lane);
+#pragma unroll
+    for (int r = 0; r < kShortPerWave; ++r) {
+        int32_t idx_nxt = -1;
+        if (r + 1 < kShortPerWave) idx_nxt = first_indices(a.col_idx, w[r + 1], lane);
+        if (w[r].row >= 0) run_item<T, LOG_G>(a, w[r], idx_cur, lane);
+        idx_cur = idx_nxt;
+    }
+}
+
+// Rows cut into segments: add their partial sums in a fixed order.  One workgroup per row;
+// thread (sl, cv) sums slots sl, sl+SL, ... of column quad cv in double, then the SL lane sums
+// are added in lane order.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void reduce_split_rows(const LayerArgs<T> a) {
+    __shared__ double red[kThreads][4];
     const int32_t k = blockIdx.x;
     if (k >= a.sched.header->n_split) return;
     const int32_t row = a.sched.split_row[k];
     const int32_t base = a.sched.split_base[k];
     const int32_t cnt = a.sched.split_cnt[k];
     const float s = a.dinv_sqrt[row];
-    for (int f = threadIdx.x; f < a.F; f += kThreads) {
-        double sum = 0.0;
-        const float* p = a.partial + (int64_t)base * a.F + f;
-        for (int32_t q = 0; q < cnt; ++q) sum += (double)p[(int64_t)q * a.F];
-        float h = s * (float)sum;
-        if (a.addend) h += load_one<T>(a.addend + (int64_t)row * a.ld_add + f);
-        if (a.out_h) store_one<T>(a.out_h + (int64_t)row * a.ld_h + f, h);
-        if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.ld_z + f, s * h);
+    const int quads = a.F / 4;
+    for (int q0 = 0; q0 < quads; q0 += kThreads) {
+        const int width = quads - q0 < kThreads ? quads - q0 : kThreads;
+        const int lanes = kThreads / width;          // slot lanes
+        const int sl = threadIdx.x / width;
+        const int cv = threadIdx.x - sl * width;
+        double sum[4] = {0.0, 0.0, 0.0, 0.0};
+        if (sl < lanes) {
+            const float* p = a.partial + (int64_t)base * a.F + (int64_t)(q0 + cv) * 4;
+            int32_t q = sl;
+            for (; q + 3 * lanes < cnt; q += 4 * lanes) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * a.F);
+                const float4 v1 = *reinterpret_cast<const float4*>(p + (int64_t)(q + lanes) * a.F);
+                const float4 v2 = *reinterpret_cast<const float4*>(p + (int64_t)(q + 2 * lanes) * a.F);
+                const float4 v3 = *reinterpret_cast<const float4*>(p + (int64_t)(q + 3 * lanes) * a.F);
+                sum[0] += (double)v0.x; sum[1] += (double)v0.y; sum[2] += (double)v0.z; sum[3] += (double)v0.w;
+                sum[0] += (double)v1.x; sum[1] += (double)v1.y; sum[2] += (double)v1.z; sum[3] += (double)v1.w;
+                sum[0] += (double)v2.x; sum[1] += (double)v2.y; sum[2] += (double)v2.z; sum[3] += (double)v2.w;
+                sum[0] += (double)v3.x; sum[1] += (double)v3.y; sum[2] += (double)v3.z; sum[3] += (double)v3.w;
+            }
+            for (; q < cnt; q += lanes) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * a.F);
+                sum[0] += (double)v0.x; sum[1] += (double)v0.y; sum[2] += (double)v0.z; sum[3] += (double)v0.w;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[threadIdx.x][e] = sum[e];
+        __syncthreads();
+        if (sl == 0) {
+            for (int l = 1; l < lanes; ++l) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum[e] += red[l * width + cv][e];
+            }
+            const int col = (q0 + cv) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float h = s * (float)sum[e];
+                if (a.addend) h += load_one<T>(a.addend + (int64_t)row * a.ld_add + col + e);
+                if (a.out_h) store_one<T>(a.out_h + (int64_t)row * a.ld_h + col + e, h);
+                if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.ld_z + col + e, s * h);
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -242,24 +324,28 @@ __global__ __launch_bounds__(kThreads) void prescale_rows(const typename T::elem
 }
 
 template <typename T>
-int32_t launch_layer(const LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream) {
+int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream) {
     const int chunks = a.F / T::kVec;
     int log_g = 0;
     while ((1 << log_g) < chunks && log_g < 6) ++log_g;
-    const int64_t max_items = sched_max_items(n, nnz);
-    const dim3 grid((unsigned)ceil_div(max_items, kWavesPerBlock));
+    const int64_t seg_blocks = nnz > kSegLen ? ceil_div(sched_max_seg_pos(nnz), kWavesPerBlock) : 0;
+    const int64_t short_blocks = ceil_div(n, (int64_t)kWavesPerBlock * kShortPerWave);
+    a.seg_blocks = (int32_t)seg_blocks;
+    const dim3 grid((unsigned)(seg_blocks + short_blocks));
     const dim3 blk(kThreads);
+    profile_mark(stream, false);
     switch (log_g) {
-        case 0: spmm_segments<T, 0><<<grid, blk, 0, stream>>>(a); break;
-        case 1: spmm_segments<T, 1><<<grid, blk, 0, stream>>>(a); break;
-        case 2: spmm_segments<T, 2><<<grid, blk, 0, stream>>>(a); break;
-        case 3: spmm_segments<T, 3><<<grid, blk, 0, stream>>>(a); break;
-        case 4: spmm_segments<T, 4><<<grid, blk, 0, stream>>>(a); break;
-        case 5: spmm_segments<T, 5><<<grid, blk, 0, stream>>>(a); break;
-        default: spmm_segments<T, 6><<<grid, blk, 0, stream>>>(a); break;
+        case 0: spmm_rows<T, 0><<<grid, blk, 0, stream>>>(a); break;
+        case 1: spmm_rows<T, 1><<<grid, blk, 0, stream>>>(a); break;
+        case 2: spmm_rows<T, 2><<<grid, blk, 0, stream>>>(a); break;
+        case 3: spmm_rows<T, 3><<<grid, blk, 0, stream>>>(a); break;
+        case 4: spmm_rows<T, 4><<<grid, blk, 0, stream>>>(a); break;
+        case 5: spmm_rows<T, 5><<<grid, blk, 0, stream>>>(a); break;
+        default: spmm_rows<T, 6><<<grid, blk, 0, stream>>>(a); break;
     }
-    E2EG_LAUNCH_CHECK("spmm_segments");
-    if (nnz > kSegLen) {  // otherwise no row can be split
+    profile_mark(stream, true);
+    E2EG_LAUNCH_CHECK("spmm_rows");
+    if (nnz > kSegLen) {  // otherwise no row can be long
         reduce_split_rows<T><<<dim3((unsigned)sched_max_split(nnz)), blk, 0, stream>>>(a);
         E2EG_LAUNCH_CHECK("reduce_split_rows");
     }
@@ -279,7 +365,7 @@ PropWs carve_prop(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F, 
     const size_t zbytes = (size_t)(n > 0 ? n : 1) * (size_t)F * esz;
     w.z[0] = c.take<char>(zbytes);
     w.z[1] = K > 1 ? c.take<char>(zbytes) : nullptr;
-    w.partial = c.take<float>((size_t)(2 * (nnz / kSegLen) + 2) * (size_t)F);
+    w.partial = c.take<float>((size_t)sched_max_seg(nnz) * (size_t)F);
     w.bytes = c.size();
     return w;
 }

@@ -1,0 +1,120 @@
+// LSD radix sort of 64-bit keys over a chosen bit range, 8-bit digits, stable.  Used to order
+// (user, item) pairs for the CSR build and row segments for the schedule.  Integer work only.
+#include "common.h"
+
+namespace e2eg {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSortItems = 8;
+constexpr int kSortTile = kThreads * kSortItems;  // keys per block
+constexpr int kWaves = kThreads / 64;
+
+// ---- radix sort, one 8-bit digit per pass --------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __restrict__ keys,
+                                                           int64_t count, int shift,
+                                                           int32_t* __restrict__ hist,
+                                                           int32_t nblocks) {
+    __shared__ int h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t idx = base + k * kThreads + threadIdx.x;
+        if (idx < count) atomicAdd(&h[(int)((keys[idx] >> shift) & 255)], 1);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+}
+
+// Stable scatter.  A block's tile is split into one contiguous chunk per wavefront; a wavefront
+// walks its chunk 64 keys at a time, ranking equal digits by lane order plus a running
+// per-wavefront digit count, so ranks follow input order.
+__global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restrict__ in,
+                                                         uint64_t* __restrict__ out,
+                                                         int64_t count, int shift,
+                                                         const int32_t* __restrict__ offs,
+                                                         int32_t nblocks) {
+    __shared__ int wave_cnt[kWaves][256];
+    for (int k = threadIdx.x; k < kWaves * 256; k += kThreads) (&wave_cnt[0][0])[k] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const int64_t chunk = (int64_t)blockIdx.x * kSortTile + (int64_t)wave * (64 * kSortItems);
+    uint64_t key[kSortItems];
+    int rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const int64_t idx = chunk + r * 64 + lane;
+        const bool valid = idx < count;
+        key[r] = valid ? in[idx] : 0ull;
+        const int d = (int)((key[r] >> shift) & 255);
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (d >> b) & 1;
+            const uint64_t bal = __ballot(valid && bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const int pre = wave_cnt[wave][d];
+        const int below = __popcll(peers & lt_mask);
+        rank[r] = pre + below;
+        if (valid && below == 0) wave_cnt[wave][d] = pre + __popcll(peers);
+    }
+    __syncthreads();
+    {
+        const int d = threadIdx.x;
+        int base = offs[(int64_t)d * nblocks + blockIdx.x];
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            int c = wave_cnt[w][d];
+            wave_cnt[w][d] = base;
+            base += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const int64_t idx = chunk + r * 64 + lane;
+        if (idx < count) {
+            const int d = (int)((key[r] >> shift) & 255);
+            out[(int64_t)wave_cnt[wave][d] + rank[r]] = key[r];
+        }
+    }
+}
+
+}  // namespace
+
+size_t radix_sort_workspace_bytes(int64_t count) {
+    const int64_t nblocks = ceil_div(count > 0 ? count : 1, kSortTile);
+    return align_up((size_t)(256 * nblocks) * sizeof(int32_t)) + scan_workspace_bytes(256 * nblocks);
+}
+
+int32_t radix_sort_u64(uint64_t** src, uint64_t** dst, int64_t count, int lo, int nbits, void* ws,
+                       hipStream_t stream) {
+    if (count <= 0) return E2EG_OK;
+    const int32_t nblocks = (int32_t)ceil_div(count, kSortTile);
+    int32_t* hist = static_cast<int32_t*>(ws);
+    void* scan_ws = static_cast<char*>(ws) + align_up((size_t)(256 * (int64_t)nblocks) * sizeof(int32_t));
+    for (int shift = lo; shift < lo + nbits; shift += 8) {
+        sort_histogram<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, hist, nblocks);
+        E2EG_LAUNCH_CHECK("sort_histogram");
+        E2EG_HIP_TRY(exclusive_scan_i32(hist, hist, (int64_t)256 * nblocks, nullptr, scan_ws, stream));
+        sort_scatter<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift, hist, nblocks);
+        E2EG_LAUNCH_CHECK("sort_scatter");
+        uint64_t* t = *src;
+        *src = *dst;
+        *dst = t;
+    }
+    return E2EG_OK;
+}
+
+int bits_for(int64_t count) {
+    int b = 1;
+    while (b < 31 && ((int64_t)1 << b) < count) ++b;
+    return b;
+}
+
+}  // namespace e2eg

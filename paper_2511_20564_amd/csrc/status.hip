@@ -1,7 +1,36 @@
 // Status strings, the thread-local error message and the version query.
 #include "common.h"
 
+#include <vector>
+
 namespace e2eg {
+
+namespace {
+struct Profile {
+    bool active = false;
+    int32_t capacity = 0;
+    std::vector<hipEvent_t> start, stop;
+};
+thread_local Profile g_profile;
+}  // namespace
+
+void profile_mark(hipStream_t stream, bool after) {
+    Profile& p = g_profile;
+    if (!p.active) return;
+    if (!after) {
+        if ((int32_t)p.start.size() >= p.capacity) return;
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        (void)hipEventRecord(e, stream);
+        p.start.push_back(e);
+    } else {
+        if (p.stop.size() >= p.start.size()) return;
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        (void)hipEventRecord(e, stream);
+        p.stop.push_back(e);
+    }
+}
 
 static thread_local char g_last_error[512] = "";
 
@@ -23,12 +52,12 @@ int32_t fail(int32_t status, const char* fmt, ...) {
 size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view) {
     Carver c(base);
     SchedView v;
-    v.max_items = sched_max_items(n, nnz);
+    v.max_seg = sched_max_seg(nnz);
+    v.max_seg_pos = sched_max_seg_pos(nnz);
     v.max_split = sched_max_split(nnz);
     v.header = c.take<SchedHeader>(1);
-    v.item_row = c.take<int32_t>(v.max_items);
-    v.item_beg = c.take<int32_t>(v.max_items);
-    v.item_slot = c.take<int32_t>(v.max_items);
+    v.seg_items = c.take<WorkItem>(v.max_seg_pos);
+    v.short_items = c.take<WorkItem>(n > 0 ? n : 1);
     v.split_row = c.take<int32_t>(v.max_split);
     v.split_base = c.take<int32_t>(v.max_split);
     v.split_cnt = c.take<int32_t>(v.max_split);
@@ -58,5 +87,38 @@ const char* e2eg_status_string(int32_t status) {
 const char* e2eg_last_error(void) { return e2eg::g_last_error; }
 
 int32_t e2eg_version(void) { return 100; }
+
+int32_t e2eg_profile_begin(int32_t capacity) {
+    if (capacity < 0) return e2eg::fail(E2EG_ERR_INVALID_ARG, "profile_begin: negative capacity");
+    e2eg::Profile& p = e2eg::g_profile;
+    for (hipEvent_t e : p.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : p.stop) (void)hipEventDestroy(e);
+    p.start.clear();
+    p.stop.clear();
+    p.capacity = capacity;
+    p.active = true;
+    return E2EG_OK;
+}
+
+int32_t e2eg_profile_end(float* h_ms, int32_t h_capacity, int32_t* h_count) {
+    e2eg::Profile& p = e2eg::g_profile;
+    p.active = false;
+    if (!h_count || (h_capacity > 0 && !h_ms)) return e2eg::fail(E2EG_ERR_NULL_PTR, "profile_end: null pointer");
+    const int32_t count = (int32_t)(p.stop.size() < p.start.size() ? p.stop.size() : p.start.size());
+    int32_t status = E2EG_OK;
+    for (int32_t k = 0; k < count; ++k) {
+        hipError_t err = hipEventSynchronize(p.stop[k]);
+        float ms = 0.0f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, p.start[k], p.stop[k]);
+        if (err != hipSuccess) status = e2eg::fail(E2EG_ERR_HIP, "profile_end: %s", hipGetErrorString(err));
+        if (k < h_capacity) h_ms[k] = ms;
+    }
+    *h_count = count;
+    for (hipEvent_t e : p.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : p.stop) (void)hipEventDestroy(e);
+    p.start.clear();
+    p.stop.clear();
+    return status;
+}
 
 }  // extern "C"

@@ -46,7 +46,7 @@ class Graph:
     sched: torch.Tensor        # uint8, opaque
 
 
-def normalize(n: int, nnz: int, row_ptr: torch.Tensor):
+def normalize(n: int, nnz: int, row_ptr: torch.Tensor, col_idx: torch.Tensor):
     """e2eg_normalize on an existing CSR -> (deg, dinv_sqrt, sched)."""
     _require_gpu()
     dev = row_ptr.device
@@ -54,7 +54,7 @@ def normalize(n: int, nnz: int, row_ptr: torch.Tensor):
     dinv = torch.empty(n, dtype=torch.float32, device=dev)
     sched = _bytes(B.e2eg_sched_bytes(n, nnz), dev)
     ws = _bytes(B.e2eg_normalize_workspace_bytes(n, nnz), dev)
-    B.e2eg_normalize(n, nnz, row_ptr, deg, dinv, sched, None, ws, None, _stream())
+    B.e2eg_normalize(n, nnz, row_ptr, col_idx, deg, dinv, sched, None, ws, None, _stream())
     return deg, dinv, sched
 
 
@@ -75,7 +75,7 @@ def build_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Te
     nnz = B.e2eg_build_csr(n_users, n_items, n_edges, users, items, flags, row_ptr, col, cap, ws, None, _stream())
     del ws
     col_idx = col[:nnz]
-    deg, dinv, sched = normalize(n, nnz, row_ptr)
+    deg, dinv, sched = normalize(n, nnz, row_ptr, col_idx)
     return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched)
 
 
