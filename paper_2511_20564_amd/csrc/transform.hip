@@ -1,19 +1,324 @@
-// e2eg_layer_transform: placeholder until the MFMA kernels land (argument checks only).
+// e2eg_layer_transform: the dense per-layer update H' = relu(P W) and its backward (paper: the
+// update function psi of the generic message-passing layer in Section 3, with the W and sigma of
+// the GraphSAGE layer in Section 3.1).
+//
+// This is the one real contraction on the path, so it runs on the matrix cores: bf16 operands,
+// fp32 accumulation, v_mfma_f32_32x32x16_bf16 (wave64; each lane feeds 8 consecutive k of one
+// row / column).  The products are computed transposed, D[out column][row], so that a lane ends
+// up holding runs of 4 consecutive output columns of ONE row and can store them as 8 bytes.
+//   forward : H  = relu(P W)        rows = nodes, k = Fin,  weight tile W^T staged in LDS
+//   dP      : dP = dZ W^T           rows = nodes, k = Fout, weight tile W staged in LDS,
+//             dZ = gH * [H > 0] formed while loading
+//   dW      : dW = P^T dZ           k = nodes: each workgroup reduces a block of nodes into an
+//             fp32 partial [Fin][Fout]; partials are added in block order by a second kernel
+//             (no atomics, reproducible).
 #include "common.h"
+
+namespace e2eg {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kRowsPerBlock = 32 * kWaves;   // one 32-row MFMA tile per wavefront
+constexpr int kMaxF = 256;
+constexpr int kPad = 8;                      // LDS row padding (elements) against bank conflicts
+constexpr int kWeightLds = 128 * (128 + kPad);  // elements; also fits 64 x (256 + kPad)
+constexpr int kTileRows = 32;                // node rows per step of the dW kernel
+constexpr int kTileLd = kTileRows + 8;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ f32x16 mfma(const uint4 a, const uint4 b, const f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Keep the bf16 halves of g where the matching half of h is > 0.
+__device__ __forceinline__ uint32_t mask_pair(uint32_t g, uint32_t h) {
+    uint32_t m = 0;
+    if (__uint_as_float(h << 16) > 0.0f) m |= 0x0000ffffu;
+    if (__uint_as_float(h & 0xffff0000u) > 0.0f) m |= 0xffff0000u;
+    return g & m;
+}
+__device__ __forceinline__ uint4 mask_vec(uint4 g, uint4 h) {
+    return make_uint4(mask_pair(g.x, h.x), mask_pair(g.y, h.y), mask_pair(g.z, h.z), mask_pair(g.w, h.w));
+}
+
+// out[r][c] = act( sum_k A[r][k] * B(c, k) ),  A = rows of `a_rows` (masked by `mask_rows` > 0
+// when MASKED), B(c, k) = TRANS_W ? w[k][c] : w[c][k].
+// grid.x: blocks of 128 rows; grid.y: groups of `ngroup` output columns.
+template <bool MASKED, bool TRANS_W, bool RELU>
+__global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restrict__ a_rows,
+                                                       const uint16_t* __restrict__ mask_rows,
+                                                       const uint16_t* __restrict__ w,
+                                                       uint16_t* __restrict__ out, int32_t n,
+                                                       int32_t kdim, int32_t ndim, int32_t w_ld,
+                                                       int32_t ngroup) {
+    __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][kdim + kPad]
+    const int ldb = kdim + kPad;
+    const int n0 = blockIdx.y * ngroup;
+    const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
+    // stage the weight tile, k contiguous per output column
+    if (TRANS_W) {
+        const int cvecs = ng / 8;
+        for (int e = threadIdx.x; e < kdim * cvecs; e += kThreads) {
+            const int k = e / cvecs, cv = e - k * cvecs;
+            const uint4 q = *reinterpret_cast<const uint4*>(w + (int64_t)k * w_ld + n0 + cv * 8);
+            const uint32_t words[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bt[(cv * 8 + 2 * j) * ldb + k] = (uint16_t)(words[j] & 0xffffu);
+                bt[(cv * 8 + 2 * j + 1) * ldb + k] = (uint16_t)(words[j] >> 16);
+            }
+        }
+    } else {
+        const int kvecs = kdim / 8;
+        for (int e = threadIdx.x; e < ng * kvecs; e += kThreads) {
+            const int c = e / kvecs, kv = e - c * kvecs;
+            *reinterpret_cast<uint4*>(bt + c * ldb + kv * 8) =
+                *reinterpret_cast<const uint4*>(w + (int64_t)(n0 + c) * w_ld + kv * 8);
+        }
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int khalf = lane >> 5;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave * 32 + l32;
+    const bool live = row < n;
+    const int ksteps = kdim / 16;
+    const int nblocks = ng / 32;
+
+    uint4 areg[kMaxF / 16];
+#pragma unroll
+    for (int ks = 0; ks < kMaxF / 16; ++ks) {
+        areg[ks] = make_uint4(0u, 0u, 0u, 0u);
+        if (ks < ksteps && live) {
+            const int64_t at = row * kdim + ks * 16 + khalf * 8;
+            areg[ks] = *reinterpret_cast<const uint4*>(a_rows + at);
+            if (MASKED) areg[ks] = mask_vec(areg[ks], *reinterpret_cast<const uint4*>(mask_rows + at));
+        }
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < kMaxF / 16; ++ks) {
+        if (ks < ksteps) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                if (nb < nblocks) {
+                    const uint4 b = *reinterpret_cast<const uint4*>(bt + (nb * 32 + l32) * ldb + ks * 16 + khalf * 8);
+                    acc[nb] = mfma(b, areg[ks], acc[nb]);  // D[out column][row]
+                }
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        if (nb < nblocks) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[i] = acc[nb][g4 * 4 + i];
+                    if (RELU && !(v[i] > 0.0f)) v[i] = 0.0f;
+                }
+                uint2 q;
+                q.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+                q.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                const int col = n0 + nb * 32 + g4 * 8 + khalf * 4;
+                *reinterpret_cast<uint2*>(out + row * ndim + col) = q;
+            }
+        }
+    }
+}
+
+// partial[blockIdx.x][c][o] = sum over this block's node rows of P[r][c] * dZ[r][o].
+// grid.y / grid.z: groups of 128 columns of P / of dZ.
+template <bool MASKED>
+__global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* __restrict__ p,
+                                                                const uint16_t* __restrict__ gh,
+                                                                const uint16_t* __restrict__ h,
+                                                                float* __restrict__ partial, int32_t n,
+                                                                int32_t fin, int32_t fout,
+                                                                int32_t rows_per_block) {
+    __shared__ __attribute__((aligned(16))) uint16_t pt[128 * kTileLd];  // P^T tile  [c][r]
+    __shared__ __attribute__((aligned(16))) uint16_t zt[128 * kTileLd];  // dZ^T tile [o][r]
+    const int c0 = blockIdx.y * 128, o0 = blockIdx.z * 128;
+    const int cg = fin - c0 < 128 ? fin - c0 : 128;
+    const int og = fout - o0 < 128 ? fout - o0 : 128;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int khalf = lane >> 5;
+    const int cv = threadIdx.x & 15;   // 8-column chunk this thread stages
+    const int tr = threadIdx.x >> 4;   // tile row 0..15 (and +16)
+    const int oblocks = og / 32;
+    const bool wave_live = wave * 32 < cg;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int ob = 0; ob < 4; ++ob)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[ob][i] = 0.0f;
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = r_begin + rows_per_block < n ? r_begin + rows_per_block : n;
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int lr = tr + half * 16;
+            const int64_t r = r0 + lr;
+            uint4 qp = make_uint4(0u, 0u, 0u, 0u), qz = qp;
+            if (r < r_end) {
+                if (cv * 8 < cg) qp = *reinterpret_cast<const uint4*>(p + r * fin + c0 + cv * 8);
+                if (cv * 8 < og) {
+                    qz = *reinterpret_cast<const uint4*>(gh + r * fout + o0 + cv * 8);
+                    if (MASKED) qz = mask_vec(qz, *reinterpret_cast<const uint4*>(h + r * fout + o0 + cv * 8));
+                }
+            }
+            const uint32_t wp[4] = {qp.x, qp.y, qp.z, qp.w};
+            const uint32_t wz[4] = {qz.x, qz.y, qz.z, qz.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pt[(cv * 8 + 2 * j) * kTileLd + lr] = (uint16_t)(wp[j] & 0xffffu);
+                pt[(cv * 8 + 2 * j + 1) * kTileLd + lr] = (uint16_t)(wp[j] >> 16);
+                zt[(cv * 8 + 2 * j) * kTileLd + lr] = (uint16_t)(wz[j] & 0xffffu);
+                zt[(cv * 8 + 2 * j + 1) * kTileLd + lr] = (uint16_t)(wz[j] >> 16);
+            }
+        }
+        __syncthreads();
+        if (wave_live) {
+#pragma unroll
+            for (int ks = 0; ks < kTileRows / 16; ++ks) {
+                const uint4 a = *reinterpret_cast<const uint4*>(pt + (wave * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
+#pragma unroll
+                for (int ob = 0; ob < 4; ++ob) {
+                    if (ob < oblocks) {
+                        const uint4 b = *reinterpret_cast<const uint4*>(zt + (ob * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
+                        acc[ob] = mfma(a, b, acc[ob]);  // D[c][o]
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (!wave_live) return;
+    float* dst = partial + (int64_t)blockIdx.x * fin * fout;
+#pragma unroll
+    for (int ob = 0; ob < 4; ++ob) {
+        if (ob < oblocks) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int c = c0 + wave * 32 + (i / 4) * 8 + khalf * 4 + (i % 4);
+                dst[(int64_t)c * fout + o0 + ob * 32 + l32] = acc[ob][i];
+            }
+        }
+    }
+}
+
+__global__ void weight_grad_reduce(const float* __restrict__ partial, int32_t nblocks, int32_t count,
+                                   float* __restrict__ gw) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    double s = 0.0;
+    for (int32_t b = 0; b < nblocks; ++b) s += (double)partial[(int64_t)b * count + e];
+    gw[e] = (float)s;
+}
+
+int32_t rows_per_block_for(int32_t n) {
+    int64_t r = ceil_div(n > 0 ? n : 1, 512);
+    r = (r + kTileRows - 1) / kTileRows * kTileRows;
+    return (int32_t)(r < 128 ? 128 : r);
+}
+
+template <bool MASKED, bool TRANS_W, bool RELU>
+void launch_dense(const void* a, const void* mask, const void* w, void* out, int32_t n, int32_t kdim,
+                  int32_t ndim, int32_t w_ld, hipStream_t stream) {
+    const int32_t ngroup = kdim > 128 ? 64 : 128;
+    const dim3 grid((unsigned)ceil_div(n, kRowsPerBlock), (unsigned)ceil_div(ndim, ngroup));
+    dense_rows<MASKED, TRANS_W, RELU><<<grid, dim3(kThreads), 0, stream>>>(
+        static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
+        static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup);
+}
+
+}  // namespace
+}  // namespace e2eg
 
 using namespace e2eg;
 
 extern "C" size_t e2eg_layer_transform_workspace_bytes(int32_t mode, int32_t n, int32_t Fin,
                                                        int32_t Fout, int32_t dtype) {
-    (void)mode; (void)n; (void)Fin; (void)Fout; (void)dtype;
-    return kAlign;
+    if (n < 0 || Fin <= 0 || Fout <= 0 || dtype != E2EG_BF16) return 0;
+    if (mode != E2EG_TRANSFORM_BWD) return kAlign;
+    const int64_t blocks = ceil_div(n > 0 ? n : 1, rows_per_block_for(n));
+    return align_up((size_t)blocks * (size_t)Fin * (size_t)Fout * sizeof(float));
 }
 
 extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
                                         int32_t dtype, int32_t relu, const void* d_P,
                                         const void* d_W, void* d_H, const void* d_gH, void* d_gP,
-                                        float* d_gW, void* ws, size_t ws_bytes, void* stream) {
-    (void)mode; (void)n; (void)Fin; (void)Fout; (void)dtype; (void)relu; (void)d_P; (void)d_W;
-    (void)d_H; (void)d_gH; (void)d_gP; (void)d_gW; (void)ws; (void)ws_bytes; (void)stream;
-    return fail(E2EG_ERR_INVALID_ARG, "layer_transform: not built yet");
+                                        float* d_gW, void* ws, size_t ws_bytes, void* stream_) {
+    const char* who = "layer_transform";
+    if (mode != E2EG_TRANSFORM_FWD && mode != E2EG_TRANSFORM_BWD)
+        return fail(E2EG_ERR_INVALID_ARG, "%s: mode %d", who, mode);
+    if (dtype != E2EG_BF16)
+        return fail(E2EG_ERR_BAD_DTYPE, "%s: only E2EG_BF16 is supported (got %d)", who, dtype);
+    if (n < 0) return fail(E2EG_ERR_INVALID_ARG, "%s: negative n", who);
+    if (Fin <= 0 || Fout <= 0 || Fin % 32 || Fout % 32 || Fin > kMaxF || Fout > kMaxF)
+        return fail(E2EG_ERR_INVALID_ARG, "%s: Fin=%d, Fout=%d must be multiples of 32 in [32, %d]", who, Fin,
+                    Fout, kMaxF);
+    if (!d_P || !d_W || !d_H) return fail(E2EG_ERR_NULL_PTR, "%s: d_P, d_W or d_H is null", who);
+    if (mode == E2EG_TRANSFORM_BWD && !d_gH) return fail(E2EG_ERR_NULL_PTR, "%s: d_gH is null", who);
+    const void* ptrs[] = {d_P, d_W, d_H, d_gH, d_gP, d_gW};
+    for (const void* q : ptrs)
+        if (q && !aligned_to(q, 16)) return fail(E2EG_ERR_INVALID_ARG, "%s: a pointer is not 16-byte aligned", who);
+    const size_t need = e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    if (mode == E2EG_TRANSFORM_FWD) {
+        if (n == 0) return E2EG_OK;
+        if (relu) launch_dense<false, true, true>(d_P, nullptr, d_W, d_H, n, Fin, Fout, Fout, stream);
+        else launch_dense<false, true, false>(d_P, nullptr, d_W, d_H, n, Fin, Fout, Fout, stream);
+        E2EG_LAUNCH_CHECK("dense_rows");
+        return E2EG_OK;
+    }
+    if (d_gP && n > 0) {
+        if (relu) launch_dense<true, false, false>(d_gH, d_H, d_W, d_gP, n, Fout, Fin, Fout, stream);
+        else launch_dense<false, false, false>(d_gH, nullptr, d_W, d_gP, n, Fout, Fin, Fout, stream);
+        E2EG_LAUNCH_CHECK("dense_rows");
+    }
+    if (d_gW) {
+        const int32_t rpb = rows_per_block_for(n);
+        const int32_t blocks = n > 0 ? (int32_t)ceil_div(n, rpb) : 0;
+        float* partial = static_cast<float*>(ws);
+        if (blocks > 0) {
+            const dim3 grid((unsigned)blocks, (unsigned)ceil_div(Fin, 128), (unsigned)ceil_div(Fout, 128));
+            const uint16_t* p = static_cast<const uint16_t*>(d_P);
+            const uint16_t* gh = static_cast<const uint16_t*>(d_gH);
+            const uint16_t* h = static_cast<const uint16_t*>(d_H);
+            if (relu) weight_grad_partial<true><<<grid, dim3(kThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
+            else weight_grad_partial<false><<<grid, dim3(kThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
+            E2EG_LAUNCH_CHECK("weight_grad_partial");
+        }
+        const int32_t count = Fin * Fout;
+        weight_grad_reduce<<<dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream>>>(partial, blocks, count, d_gW);
+        E2EG_LAUNCH_CHECK("weight_grad_reduce");
+    }
+    return E2EG_OK;
 }

@@ -1,0 +1,116 @@
+"""GPU parity of the dense per-layer update (bf16 MFMA) and of the mini-batch pipeline
+propagate -> transform -> ReLU, forward and backward, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from parity import assert_close, errors, to_device, to_f64
+from workloads import make_config, make_features
+
+pytestmark = pytest.mark.gpu
+
+DW_TOL = 1e-3   # dW is stored in fp32; its error is fp32 accumulation over the n node rows
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2511_20564_amd.device as d
+    d.B.load_library()
+    return d
+
+
+def bits(t):
+    """bf16 cuda tensor -> uint16 numpy bit patterns (what the oracle reads)."""
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("n", [1, 31, 1000, 4133])
+@pytest.mark.parametrize("Fin,Fout", [(128, 128), (32, 64), (64, 32), (96, 160), (256, 256)])
+@pytest.mark.parametrize("relu", [True, False])
+def test_transform_fwd_bwd(dev, oracle, n, Fin, Fout, relu):
+    Pb = make_features(n, Fin, 0.5, 11, "bf16")
+    Wb = make_features(Fin, Fout, (1.0 / Fin) ** 0.5, 12, "bf16")
+    gHb = make_features(n, Fout, 1.0, 13, "bf16")
+    P, W, gH = to_device(Pb, "bf16"), to_device(Wb, "bf16"), to_device(gHb, "bf16")
+    H = dev.layer_transform_fwd(P, W, relu)
+    torch.cuda.synchronize()
+    Zr, Hr = oracle.transform_fwd(Pb, Wb, relu)
+    scale = np.abs(oracle.as_f64(Pb)) @ np.abs(oracle.as_f64(Wb))
+    # a Z within rounding distance of 0 may land on either side of the ReLU: both are right
+    got = to_f64(H)
+    if relu:
+        near0 = np.abs(Zr) <= 2.0 ** -7 * scale
+        ok = near0 & ((got == 0) | (np.abs(got - Zr) <= 2e-2 * scale))
+        got = np.where(ok, Hr, got)
+    assert_close(got, Hr, scale, "bf16", "transform fwd")
+    # backward, masks taken from the GPU's own H so both sides decide alike
+    gP, gW = dev.layer_transform_bwd(P, W, H, gH, relu)
+    torch.cuda.synchronize()
+    dPr, dWr = oracle.transform_bwd(Pb, Wb, bits(H), gHb, relu)
+    dZabs = np.abs(oracle.as_f64(gHb)) * ((oracle.as_f64(bits(H)) > 0) if relu else 1.0)
+    assert_close(to_f64(gP), dPr, dZabs @ np.abs(oracle.as_f64(Wb)).T, "bf16", "transform dP")
+    comp, norm = errors(to_f64(gW), dWr, np.abs(oracle.as_f64(Pb)).T @ dZabs)
+    assert comp <= DW_TOL and norm <= DW_TOL, (comp, norm)
+
+
+def test_minibatch_pipeline(dev, oracle):
+    """Sampled two-hop subgraph: per layer P = A^ H, Z = P W, ReLU between layers (none after
+    the last), then the full backward.  Each GPU stage is checked against the oracle applied to
+    the GPU's own inputs of that stage (bf16 arrays), and the forward result end to end."""
+    c = make_config(4, scale=0.05)
+    run_minibatch(dev, oracle, c)
+
+
+def run_minibatch(dev, oracle, c):
+    K, F = c["K"], c["F"]
+    u = torch.from_numpy(c["users"]).cuda()
+    i = torch.from_numpy(c["items"]).cuda()
+    g = dev.build_graph(c["n_users"], c["n_items"], u, i)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    assert np.array_equal(g.row_ptr.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(g.col_idx.cpu().numpy(), col)
+    W = [to_device(w, "bf16") for w in c["W"]]
+    H = [to_device(c["X0"], "bf16")]
+    P = []
+    # ---- forward
+    for l in range(K):
+        P.append(dev.propagate_fwd(g, H[l], 1))
+        H.append(dev.layer_transform_fwd(P[l], W[l], relu=(l < K - 1)))
+    torch.cuda.synchronize()
+    absW = [np.abs(oracle.as_f64(w)) for w in c["W"]]
+    for l in range(K):
+        ref = oracle.propagate_layer(row_ptr, col, oracle.as_f64(bits(H[l])))
+        sc = oracle.propagate_layer(row_ptr, col, np.abs(oracle.as_f64(bits(H[l]))))
+        assert_close(to_f64(P[l]), ref, sc, "bf16", f"P{l + 1}")
+        relu = l < K - 1
+        Zr, Hr = oracle.transform_fwd(bits(P[l]), c["W"][l], relu)
+        sc = np.abs(oracle.as_f64(bits(P[l]))) @ absW[l]
+        got = to_f64(H[l + 1])
+        if relu:
+            near0 = np.abs(Zr) <= 2.0 ** -7 * sc
+            got = np.where(near0 & ((got == 0) | (np.abs(got - Zr) <= 2e-2 * sc)), Hr, got)
+        assert_close(got, Hr, sc, "bf16", f"H{l + 1}")
+    # end to end, oracle never rounding: bound the drift of the whole forward chain
+    Ht = oracle.as_f64(c["X0"])
+    for l in range(K):
+        Ht = oracle.transform_fwd(oracle.propagate_layer(row_ptr, col, Ht), c["W"][l], l < K - 1)[1]
+    drift = np.abs(to_f64(H[K]) - Ht).max() / np.abs(Ht).max()
+    assert drift < 5e-2, drift
+    # ---- backward
+    gH = to_device(c["gY"], "bf16")
+    for l in range(K - 1, -1, -1):
+        relu = l < K - 1
+        gP, gW = dev.layer_transform_bwd(P[l], W[l], H[l + 1], gH, relu)
+        gHprev = dev.propagate_bwd(g, gP, 1)
+        torch.cuda.synchronize()
+        dPr, dWr = oracle.transform_bwd(bits(P[l]), c["W"][l], bits(H[l + 1]), bits(gH), relu)
+        dZabs = np.abs(oracle.as_f64(bits(gH))) * ((oracle.as_f64(bits(H[l + 1])) > 0) if relu else 1.0)
+        assert_close(to_f64(gP), dPr, dZabs @ absW[l].T, "bf16", f"dP{l + 1}")
+        comp, norm = errors(to_f64(gW), dWr, np.abs(oracle.as_f64(bits(P[l]))).T @ dZabs)
+        assert comp <= DW_TOL and norm <= DW_TOL, (l, comp, norm)
+        ref = oracle.propagate_layer_transposed(row_ptr, col, oracle.as_f64(bits(gP)))
+        sc = oracle.propagate_layer_transposed(row_ptr, col, np.abs(oracle.as_f64(bits(gP))))
+        assert_close(to_f64(gHprev), ref, sc, "bf16", f"gH{l}")
+        gH = gHprev
