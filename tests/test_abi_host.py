@@ -1,0 +1,166 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+the header declares, the binding covers them all, and argument errors are caught before any
+device work is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "e2eg.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_20564_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_20564_amd import build
+        build.build(verbose=False)
+    binding.load_library()
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(e2eg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_entry_points():
+    names = declared_functions()
+    for required in ("e2eg_build_csr", "e2eg_normalize", "e2eg_propagate_fwd", "e2eg_propagate_bwd",
+                     "e2eg_layer_transform"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in e2eg.h but not exported"
+
+
+def test_binding_mirrors_the_header(B):
+    assert sorted(B.SIGNATURES) == declared_functions()
+    for name in declared_functions():
+        assert hasattr(B, name), f"binding has no wrapper named {name}"
+
+
+def test_status_strings(B):
+    assert B.e2eg_status_string(0) == "ok"
+    for code in range(-8, 0):
+        assert B.e2eg_status_string(code) not in ("ok", "unknown status")
+    assert B.e2eg_status_string(-99) == "unknown status"
+    assert B.e2eg_version() >= 100
+
+
+def test_workspace_queries_are_pure_host_functions(B):
+    assert B.e2eg_build_csr_workspace_bytes(1000, 500, 20000) >= 2 * 8 * 20000
+    assert B.e2eg_build_csr_workspace_bytes(-1, 5, 5) == 0
+    assert B.e2eg_sched_bytes(3000, 43000) > 16 * 3000
+    assert B.e2eg_normalize_workspace_bytes(3000, 43000) > 12 * 3000
+    one = B.e2eg_propagate_workspace_bytes(3000, 43000, B.E2EG_F32, 64, 1)
+    two = B.e2eg_propagate_workspace_bytes(3000, 43000, B.E2EG_F32, 64, 2)
+    assert two >= one + 3000 * 64 * 4 > 0
+    assert B.e2eg_propagate_workspace_bytes(3000, 43000, 7, 64, 2) == 0
+    assert B.e2eg_layer_transform_workspace_bytes(B.E2EG_TRANSFORM_BWD, 1000, 128, 128, B.E2EG_BF16) >= 128 * 128 * 4
+    for q in (B.e2eg_sched_bytes(10, 10), one, two):
+        assert q % 256 == 0
+
+
+FAKE = 0x1000  # non-null, 256-byte aligned; never dereferenced because validation fails first
+
+
+def status_of(B, fn, *args):
+    with pytest.raises(B.E2egError) as e:
+        fn(*args)
+    assert B.e2eg_last_error() != ""
+    return e.value.status
+
+
+def test_build_csr_argument_errors(B):
+    f = B.e2eg_build_csr
+    assert status_of(B, f, -1, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 100, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 2, FAKE, FAKE, 100, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 5, 5, 3, None, FAKE, 1, FAKE, FAKE, 100, FAKE, 1 << 20) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 1, None, FAKE, 100, FAKE, 1 << 20) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 15, FAKE, 1 << 20) == B.E2EG_ERR_CAPACITY
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 16, None, 0) == B.E2EG_ERR_WORKSPACE
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 16, FAKE + 8, 1 << 20) == B.E2EG_ERR_WORKSPACE
+    assert status_of(B, f, 5, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 16, FAKE, 64) == B.E2EG_ERR_WORKSPACE
+    # nnz bound 2*E + n beyond int32
+    big = 1_100_000_000
+    assert status_of(B, f, 5, 5, big, FAKE, FAKE, 1, FAKE, FAKE, 3 * big, FAKE, 1 << 40) == B.E2EG_ERR_OVERFLOW
+    assert status_of(B, f, 0, 5, 3, FAKE, FAKE, 1, FAKE, FAKE, 100, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+
+
+def test_normalize_argument_errors(B):
+    f = B.e2eg_normalize
+    assert status_of(B, f, -1, 10, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 10, 1 << 31, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, FAKE, 1 << 40) == B.E2EG_ERR_OVERFLOW
+    assert status_of(B, f, 10, 20, None, FAKE, FAKE, FAKE, FAKE, 1 << 20, FAKE, 1 << 20) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 10, 20, FAKE, None, FAKE, FAKE, FAKE, 1 << 20, FAKE, 1 << 20) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 10, 20, FAKE, FAKE, FAKE, FAKE, FAKE, 16, FAKE, 1 << 20) == B.E2EG_ERR_CAPACITY
+    assert status_of(B, f, 10, 20, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, FAKE, 16) == B.E2EG_ERR_WORKSPACE
+
+
+def test_propagate_argument_errors(B):
+    f = B.e2eg_propagate_fwd
+    ok = dict(n=10, nnz=20, rp=FAKE, ci=FAKE, di=FAKE, sc=FAKE, dt=B.E2EG_F32, F=64, K=2, x=FAKE, ldx=64, o=FAKE,
+              ldo=64, ls=0, ws=FAKE, wsb=1 << 30)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return status_of(B, f, a["n"], a["nnz"], a["rp"], a["ci"], a["di"], a["sc"], a["dt"], a["F"], a["K"],
+                         a["x"], a["ldx"], a["o"], a["ldo"], a["ls"], a["ws"], a["wsb"])
+
+    assert call(n=-1) == B.E2EG_ERR_INVALID_ARG
+    assert call(nnz=1 << 31) == B.E2EG_ERR_OVERFLOW
+    assert call(dt=5) == B.E2EG_ERR_BAD_DTYPE
+    assert call(F=66) == B.E2EG_ERR_INVALID_ARG            # fp32 rows are read 16 bytes at a time
+    assert call(dt=B.E2EG_BF16, F=68) == B.E2EG_ERR_INVALID_ARG
+    assert call(K=0) == B.E2EG_ERR_INVALID_ARG
+    assert call(rp=None) == B.E2EG_ERR_NULL_PTR
+    assert call(x=None) == B.E2EG_ERR_NULL_PTR
+    assert call(x=FAKE + 4) == B.E2EG_ERR_INVALID_ARG       # misaligned
+    assert call(ldx=60) == B.E2EG_ERR_INVALID_ARG           # ld < F
+    assert call(ldo=66) == B.E2EG_ERR_INVALID_ARG
+    assert call(ls=100) == B.E2EG_ERR_INVALID_ARG           # 0 < layer_stride < n*ldo
+    assert call(ws=None) == B.E2EG_ERR_WORKSPACE
+    assert call(wsb=128) == B.E2EG_ERR_WORKSPACE
+    g = B.e2eg_propagate_bwd
+    assert status_of(B, g, 10, 20, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 64, 2, None, 64, None, 0, FAKE, 64, FAKE,
+                     1 << 30) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, g, 10, 20, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 64, 3, FAKE, 64, FAKE, 8, FAKE, 64, FAKE,
+                     1 << 30) == B.E2EG_ERR_INVALID_ARG      # direct-term stride too small
+
+
+def test_layer_transform_argument_errors(B):
+    f = B.e2eg_layer_transform
+    assert status_of(B, f, 9, 10, 128, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 20) \
+        == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 0, 10, 128, 128, B.E2EG_F32, 1, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 20) \
+        == B.E2EG_ERR_BAD_DTYPE
+    assert status_of(B, f, 0, 10, 100, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 20) \
+        == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 0, 10, 128, 512, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 20) \
+        == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 0, 10, 128, 128, B.E2EG_BF16, 1, None, FAKE, FAKE, None, None, None, FAKE, 1 << 20) \
+        == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 1, 10, 128, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 1 << 20) \
+        == B.E2EG_ERR_NULL_PTR                                # backward without d_gH
+    assert status_of(B, f, 1, 10, 128, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16) \
+        == B.E2EG_ERR_WORKSPACE
+
+
+def test_profile_aid_rejects_bad_arguments(B):
+    assert status_of(B, B.e2eg_profile_begin, -1) == B.E2EG_ERR_INVALID_ARG
+
+
+def test_device_helpers_refuse_to_run_without_gpu():
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    import paper_2511_20564_amd.device as dev
+    with pytest.raises(RuntimeError):
+        dev.propagate_fwd(None, torch.zeros(4, 4), 1)

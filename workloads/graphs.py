@@ -271,6 +271,8 @@ def _cache_path(tag: str):
     root = os.environ.get("E2EG_WORKLOAD_CACHE", "")
     if not root:
         return None
+    if tag.startswith("xlarge|"):      # too large to be worth writing to disk
+        return None
     os.makedirs(root, exist_ok=True)
     return os.path.join(root, hashlib.sha1(tag.encode()).hexdigest()[:16] + ".npz")
 
