@@ -7,22 +7,36 @@
 // so a layer is an UNWEIGHTED sum of neighbour rows of Z followed by one scale per output row:
 // the only per-edge datum read is the 4-byte column index.  Z(0) is made by one streaming
 // pre-scale pass; every later Z(l) is written by the layer that produces it.  Layers the caller
-// asked for are stored as H(l); layers it did not ask for exist only as Z(l).
+// asked for are stored as H(l); layers it did not ask for exist only as Z(l).  Every Z buffer
+// carries one extra all-zero row (index n): "no neighbour" lanes read it, which keeps the
+// gather loop free of per-lane predicates.
 //
 // Kernel shape (wave64): a group of G = 16-byte-chunks-per-row lanes reads one neighbour row with
-// 16-byte loads, so a wavefront gathers 64/G neighbour rows per load instruction, several
+// 16-byte loads, so a wavefront gathers 64/G neighbour rows per load instruction, eight
 // instructions in flight.  Column indices are fetched 64 at a time (one coalesced load) and
 // handed to the groups through cross-lane moves, the next 64 requested before the current
-// gathers are consumed.  Work items come from the schedule: whole short rows (several per
+// gathers are consumed.  Measured on gfx950 the first version of this loop was bound by vector
+// ALU issue, not by memory (about 36 VALU instructions per 16-byte gather, most of them bf16
+// unpacking, fp32 adds and 64-bit address arithmetic), so the loop is built to need few VALU
+// instructions: byte offsets are 32-bit (one v_mad_u32_u24 per gather, scalar base address),
+// there is no per-lane predicate, and bf16 results are packed by v_cvt_pk_bf16_f32.
+// Work items come from the schedule: whole short rows (several per
 // wavefront) and segments of long rows; segments leave fp32 partial sums that a second kernel
 // adds in a fixed order (in double), so there are no floating-point atomics and results are
 // reproducible.
 #include "common.h"
 
+#include <type_traits>
+
 namespace e2eg {
 namespace {
 
 constexpr int kThreads = 64 * kWavesPerBlock;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // ---- storage types ---------------------------------------------------------------------------
 struct F32 {
@@ -36,15 +50,14 @@ struct BF16 {
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// Two floats -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <typename T>
 __device__ __forceinline__ void load_vec(const typename T::elem* p, float (&v)[T::kVec]);
-
 template <>
 __device__ __forceinline__ void load_vec<F32>(const float* p, float (&v)[4]) {
     const float4 q = *reinterpret_cast<const float4*>(p);
@@ -59,21 +72,19 @@ __device__ __forceinline__ void load_vec<BF16>(const uint16_t* p, float (&v)[8])
     v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
 }
 
+// Layer outputs and partial sums are written once and not read again by the same kernel:
+// streaming stores keep them from displacing the feature rows the gathers reuse in L2.
 template <typename T>
 __device__ __forceinline__ void store_vec(typename T::elem* p, const float (&v)[T::kVec]);
-
 template <>
 __device__ __forceinline__ void store_vec<F32>(float* p, const float (&v)[4]) {
-    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    const f32x4 q = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
 }
 template <>
 __device__ __forceinline__ void store_vec<BF16>(uint16_t* p, const float (&v)[8]) {
-    uint4 q;
-    q.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-    q.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-    q.z = f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16);
-    q.w = f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16);
-    *reinterpret_cast<uint4*>(p) = q;
+    const u32x4 q = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+    __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(p));
 }
 
 template <typename T>
@@ -88,7 +99,7 @@ __device__ __forceinline__ void store_one(typename T::elem* p, float v);
 template <>
 __device__ __forceinline__ void store_one<F32>(float* p, float v) { *p = v; }
 template <>
-__device__ __forceinline__ void store_one<BF16>(uint16_t* p, float v) { *p = (uint16_t)f32_to_bf16(v); }
+__device__ __forceinline__ void store_one<BF16>(uint16_t* p, float v) { *p = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu); }
 
 // ---- one layer --------------------------------------------------------------------------------
 template <typename T>
@@ -97,34 +108,50 @@ struct LayerArgs {
     const int32_t* col_idx;
     const float* dinv_sqrt;
     SchedView sched;
-    const typename T::elem* zin;  // Z(l) = S H(l), [n][F]
-    int64_t ld_zin;
+    const typename T::elem* zin;  // Z(l) = S H(l), [n + 1][F], row n all zero
     typename T::elem* out_h;      // H(l+1) or null
     int64_t ld_h;
-    typename T::elem* out_z;      // Z(l+1) = S H(l+1) or null
-    int64_t ld_z;
+    typename T::elem* out_z;      // Z(l+1) = S H(l+1), [n + 1][F], or null
     const typename T::elem* addend;  // direct term added to H(l+1) before scaling, or null
     int64_t ld_add;
     float* partial;               // [slots][F] fp32
     int32_t F;
+    int32_t zero_row;             // = n
     int32_t seg_blocks;           // workgroups that walk seg_items; the rest walk short_items
 };
 
-// 16 raw bytes of a feature row -> added into fp32 accumulators.
+// Accumulators of one work item: acc[v] holds this lane's 16-byte chunk as fp32; the NB lane
+// groups hold separate partial sums that are added across groups at the end.
 template <typename T>
-__device__ __forceinline__ void accumulate(float (&acc)[T::kVec], const uint4 q);
-template <>
-__device__ __forceinline__ void accumulate<F32>(float (&acc)[4], const uint4 q) {
-    acc[0] += __uint_as_float(q.x); acc[1] += __uint_as_float(q.y);
-    acc[2] += __uint_as_float(q.z); acc[3] += __uint_as_float(q.w);
-}
-template <>
-__device__ __forceinline__ void accumulate<BF16>(float (&acc)[8], const uint4 q) {
-    acc[0] += __uint_as_float(q.x << 16); acc[1] += __uint_as_float(q.x & 0xffff0000u);
-    acc[2] += __uint_as_float(q.y << 16); acc[3] += __uint_as_float(q.y & 0xffff0000u);
-    acc[4] += __uint_as_float(q.z << 16); acc[5] += __uint_as_float(q.z & 0xffff0000u);
-    acc[6] += __uint_as_float(q.w << 16); acc[7] += __uint_as_float(q.w & 0xffff0000u);
-}
+struct Sum {
+    float acc[T::kVec];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int v = 0; v < T::kVec; ++v) acc[v] = 0.0f;
+    }
+    __device__ __forceinline__ void add(const uint4 q) {
+        if constexpr (std::is_same<T, F32>::value) {
+            acc[0] += __uint_as_float(q.x); acc[1] += __uint_as_float(q.y);
+            acc[2] += __uint_as_float(q.z); acc[3] += __uint_as_float(q.w);
+        } else {
+            acc[0] += __uint_as_float(q.x << 16); acc[1] += __uint_as_float(q.x & 0xffff0000u);
+            acc[2] += __uint_as_float(q.y << 16); acc[3] += __uint_as_float(q.y & 0xffff0000u);
+            acc[4] += __uint_as_float(q.z << 16); acc[5] += __uint_as_float(q.z & 0xffff0000u);
+            acc[6] += __uint_as_float(q.w << 16); acc[7] += __uint_as_float(q.w & 0xffff0000u);
+        }
+    }
+    // -> out[] = the chunk's total, valid in lanes of group 0
+    template <int LOG_G>
+    __device__ __forceinline__ void total(float (&out)[T::kVec]) {
+#pragma unroll
+        for (int off = 1 << LOG_G; off < 64; off <<= 1) {
+#pragma unroll
+            for (int v = 0; v < T::kVec; ++v) acc[v] += __shfl_xor(acc[v], off);
+        }
+#pragma unroll
+        for (int v = 0; v < T::kVec; ++v) out[v] = acc[v];
+    }
+};
 
 // Per-row finish: h = s * sum (+ addend); store H and/or Z = s * h.
 template <typename T>
@@ -144,19 +171,33 @@ __device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t row, i
     if (a.out_z) {
 #pragma unroll
         for (int v = 0; v < T::kVec; ++v) h[v] *= s;
-        store_vec<T>(a.out_z + (int64_t)row * a.ld_z + col, h);
+        store_vec<T>(a.out_z + (int64_t)row * a.F + col, h);
     }
 }
 
-// First (up to) 64 column indices of a work item, one per lane; -1 beyond its end.
-__device__ __forceinline__ int32_t first_indices(const int32_t* __restrict__ col_idx, const WorkItem& w,
-                                                 int lane) {
-    return (w.row >= 0 && lane < w.end - w.beg) ? col_idx[w.beg + lane] : -1;
+// First (up to) 64 column indices of a work item, one per lane; the zero row beyond its end.
+template <typename T>
+__device__ __forceinline__ int32_t first_indices(const LayerArgs<T>& a, const WorkItem& w, int lane) {
+    return (w.row >= 0 && lane < w.end - w.beg) ? __builtin_nontemporal_load(a.col_idx + w.beg + lane)
+                                                : a.zero_row;
+}
+
+// 16 bytes of row j at byte offset `lane_off` inside the row.  NARROW: the table is below 4 GiB
+// and has fewer than 2^24 rows, so the offset is one 24-bit multiply-add on a scalar base.
+template <typename T, bool NARROW>
+__device__ __forceinline__ uint4 gather16(const LayerArgs<T>& a, int32_t j, uint32_t row_bytes,
+                                          uint32_t lane_off) {
+    const char* base = reinterpret_cast<const char*>(a.zin);
+    if constexpr (NARROW) {
+        return *reinterpret_cast<const uint4*>(base + (__umul24((uint32_t)j, row_bytes) + lane_off));
+    } else {
+        return *reinterpret_cast<const uint4*>(base + ((uint64_t)(uint32_t)j * row_bytes + lane_off));
+    }
 }
 
 // Sums the neighbour rows of one work item and stores the row (or its partial sum).
 // `idx_first` holds the item's first 64 column indices, fetched ahead by the caller.
-template <typename T, int LOG_G>
+template <typename T, int LOG_G, bool NARROW>
 __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w, const int32_t idx_first,
                                          const int lane) {
     constexpr int G = 1 << LOG_G;    // lanes per neighbour row
@@ -166,49 +207,55 @@ __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w
     const int g = lane >> LOG_G;
     const int c = lane & (G - 1);
     const int chunks = a.F / V;
+    const uint32_t row_bytes = (uint32_t)a.F * (uint32_t)sizeof(typename T::elem);
 
-    for (int cb = 0; cb < chunks; cb += G) {
+    for (int cb = 0; cb < chunks; cb += G) {   // more than one pass only for rows wider than 1 KiB
         const int cc = cb + c;
-        const bool active = cc < chunks;
-        const typename T::elem* zcol = a.zin + (active ? cc : 0) * V;
-        float acc[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+        const bool active = cc < chunks;       // idle lanes re-read chunk 0; their sums are dropped
+        const uint32_t lane_off = active ? (uint32_t)cc * 16u : 0u;
+        Sum<T> sum;
+        sum.clear();
 
         int32_t idx = idx_first;
         for (int32_t base = w.beg; base < w.end; base += 64) {
             const int cnt = w.end - base < 64 ? w.end - base : 64;
-            int32_t idx_next = -1;  // next 64 indices, requested before this block's gathers
-            if (base + 64 < w.end && lane < w.end - base - 64) idx_next = a.col_idx[base + 64 + lane];
-            for (int t = 0; t < cnt; t += U * NB) {
+            int32_t idx_next = a.zero_row;  // next 64 indices, requested before this block's gathers
+            if (base + 64 < w.end && lane < w.end - base - 64)
+                idx_next = __builtin_nontemporal_load(a.col_idx + base + 64 + lane);
+            int t = 0;
+            for (; t + U * NB <= cnt; t += U * NB) {
                 uint4 q[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int src = t + u * NB + g;
-                    const int32_t j = __shfl(idx, src & 63);
-                    q[u] = make_uint4(0u, 0u, 0u, 0u);
-                    if (src < cnt && j >= 0)
-                        q[u] = *reinterpret_cast<const uint4*>(zcol + (int64_t)j * a.ld_zin);
-                }
+                for (int u = 0; u < U; ++u)
+                    q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
 #pragma unroll
-                for (int u = 0; u < U; ++u) accumulate<T>(acc, q[u]);
+                for (int u = 0; u < U; ++u) sum.add(q[u]);
+            }
+            if (t < cnt) {  // last, partial batch: whole load instructions are skipped uniformly,
+                            // lanes past the end inside a kept instruction read the zero row
+                const int live = (cnt - t + NB - 1) / NB;
+                uint4 q[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (u < live) q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (u < live) sum.add(q[u]);
             }
             idx = idx_next;
         }
-        // add the NB group sums together (lanes with equal c)
-#pragma unroll
-        for (int off = G; off < 64; off <<= 1) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] += __shfl_xor(acc[v], off);
-        }
+        float tot[V];
+        sum.template total<LOG_G>(tot);
         if (g == 0 && active) {
             if (w.slot < 0) {
-                finish_vec<T>(a, w.row, cc * V, acc);
+                finish_vec<T>(a, w.row, cc * V, tot);
             } else {
                 float* p = a.partial + (int64_t)w.slot * a.F + cc * V;
 #pragma unroll
-                for (int v = 0; v < V; v += 4)
-                    *reinterpret_cast<float4*>(p + v) = make_float4(acc[v], acc[v + 1], acc[v + 2], acc[v + 3]);
+                for (int v = 0; v < V; v += 4) {
+                    const f32x4 o = {tot[v], tot[v + 1], tot[v + 2], tot[v + 3]};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p + v));
+                }
             }
         }
     }
@@ -217,14 +264,14 @@ __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w
 // Workgroups [0, seg_blocks): one segment of a long row per wavefront (placed per XCD by the
 // schedule).  Workgroups beyond: kShortPerWave whole rows per wavefront, the next row's column
 // indices requested while the current row's gathers are in flight.
-template <typename T, int LOG_G>
+template <typename T, int LOG_G, bool NARROW>
 __global__ __launch_bounds__(kThreads) void spmm_rows(const LayerArgs<T> a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if ((int32_t)blockIdx.x < a.seg_blocks) {
         const WorkItem w = a.sched.seg_items[(int64_t)blockIdx.x * kWavesPerBlock + wave];
         if (w.row < 0) return;
-        run_item<T, LOG_G>(a, w, first_indices(a.col_idx, w, lane), lane);
+        run_item<T, LOG_G, NARROW>(a, w, first_indices<T>(a, w, lane), lane);
         return;
     }
     const int64_t first = (((int64_t)blockIdx.x - a.seg_blocks) * kWavesPerBlock + wave) * kShortPerWave;
@@ -234,12 +281,12 @@ __global__ __launch_bounds__(kThreads) void spmm_rows(const LayerArgs<T> a) {
 #pragma unroll
     for (int r = 0; r < kShortPerWave; ++r)
         w[r] = first + r < n_short ? a.sched.short_items[first + r] : WorkItem{-1, 0, 0, -1};
-    int32_t idx_cur = first_indices(a.col_idx, w[0], lane);
+    int32_t idx_cur = first_indices<T>(a, w[0], lane);
 #pragma unroll
     for (int r = 0; r < kShortPerWave; ++r) {
-        int32_t idx_nxt = -1;
-        if (r + 1 < kShortPerWave) idx_nxt = first_indices(a.col_idx, w[r + 1], lane);
-        if (w[r].row >= 0) run_item<T, LOG_G>(a, w[r], idx_cur, lane);
+        int32_t idx_nxt = a.zero_row;
+        if (r + 1 < kShortPerWave) idx_nxt = first_indices<T>(a, w[r + 1], lane);
+        if (w[r].row >= 0) run_item<T, LOG_G, NARROW>(a, w[r], idx_cur, lane);
         idx_cur = idx_nxt;
     }
 }
@@ -295,32 +342,55 @@ __global__ __launch_bounds__(kThreads) void reduce_split_rows(const LayerArgs<T>
                 float h = s * (float)sum[e];
                 if (a.addend) h += load_one<T>(a.addend + (int64_t)row * a.ld_add + col + e);
                 if (a.out_h) store_one<T>(a.out_h + (int64_t)row * a.ld_h + col + e, h);
-                if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.ld_z + col + e, s * h);
+                if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.F + col + e, s * h);
             }
         }
         __syncthreads();
     }
 }
 
-// Z(0) = S X(0): one streaming pass, 16 bytes per thread.
+// Z(0) = S X(0): one streaming pass, 16 bytes per thread.  Also clears the zero rows (index n)
+// of both Z buffers.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void prescale_rows(const typename T::elem* __restrict__ x,
                                                           int64_t ldx,
                                                           const float* __restrict__ dinv_sqrt,
                                                           typename T::elem* __restrict__ z,
-                                                          int64_t ldz, int64_t n, int32_t F) {
+                                                          typename T::elem* __restrict__ z_other,
+                                                          int64_t n, int32_t F) {
     constexpr int V = T::kVec;
     const int chunks = F / V;
     const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (id >= n * chunks) return;
+    if (id >= (n + 1) * chunks) return;
     const int64_t row = id / chunks;
     const int col = (int)(id - row * chunks) * V;
     float v[V];
+    if (row == n) {
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[k] = 0.0f;
+        store_vec<T>(z + row * F + col, v);
+        if (z_other) store_vec<T>(z_other + row * F + col, v);
+        return;
+    }
     load_vec<T>(x + row * ldx + col, v);
     const float s = dinv_sqrt[row];
 #pragma unroll
     for (int k = 0; k < V; ++k) v[k] *= s;
-    store_vec<T>(z + row * ldz + col, v);
+    store_vec<T>(z + row * F + col, v);
+}
+
+template <typename T, bool NARROW>
+void launch_spmm(int log_g, dim3 grid, const LayerArgs<T>& a, hipStream_t stream) {
+    const dim3 blk(kThreads);
+    switch (log_g) {
+        case 0: spmm_rows<T, 0, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 1: spmm_rows<T, 1, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 2: spmm_rows<T, 2, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 3: spmm_rows<T, 3, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 4: spmm_rows<T, 4, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 5: spmm_rows<T, 5, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        default: spmm_rows<T, 6, NARROW><<<grid, blk, 0, stream>>>(a); break;
+    }
 }
 
 template <typename T>
@@ -331,22 +401,17 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const int64_t seg_blocks = nnz > kSegLen ? ceil_div(sched_max_seg_pos(nnz), kWavesPerBlock) : 0;
     const int64_t short_blocks = ceil_div(n, (int64_t)kWavesPerBlock * kShortPerWave);
     a.seg_blocks = (int32_t)seg_blocks;
+    a.zero_row = (int32_t)n;
     const dim3 grid((unsigned)(seg_blocks + short_blocks));
-    const dim3 blk(kThreads);
+    const uint64_t table_bytes = (uint64_t)(n + 1) * (uint64_t)a.F * sizeof(typename T::elem);
+    const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
     profile_mark(stream, false);
-    switch (log_g) {
-        case 0: spmm_rows<T, 0><<<grid, blk, 0, stream>>>(a); break;
-        case 1: spmm_rows<T, 1><<<grid, blk, 0, stream>>>(a); break;
-        case 2: spmm_rows<T, 2><<<grid, blk, 0, stream>>>(a); break;
-        case 3: spmm_rows<T, 3><<<grid, blk, 0, stream>>>(a); break;
-        case 4: spmm_rows<T, 4><<<grid, blk, 0, stream>>>(a); break;
-        case 5: spmm_rows<T, 5><<<grid, blk, 0, stream>>>(a); break;
-        default: spmm_rows<T, 6><<<grid, blk, 0, stream>>>(a); break;
-    }
+    if (narrow) launch_spmm<T, true>(log_g, grid, a, stream);
+    else launch_spmm<T, false>(log_g, grid, a, stream);
     profile_mark(stream, true);
     E2EG_LAUNCH_CHECK("spmm_rows");
     if (nnz > kSegLen) {  // otherwise no row can be long
-        reduce_split_rows<T><<<dim3((unsigned)sched_max_split(nnz)), blk, 0, stream>>>(a);
+        reduce_split_rows<T><<<dim3((unsigned)sched_max_split(nnz)), dim3(kThreads), 0, stream>>>(a);
         E2EG_LAUNCH_CHECK("reduce_split_rows");
     }
     return E2EG_OK;
@@ -362,7 +427,7 @@ PropWs carve_prop(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F, 
     Carver c(base);
     PropWs w;
     const size_t esz = dtype == E2EG_F32 ? 4 : 2;
-    const size_t zbytes = (size_t)(n > 0 ? n : 1) * (size_t)F * esz;
+    const size_t zbytes = (size_t)(n + 1) * (size_t)F * esz;  // one extra all-zero row
     w.z[0] = c.take<char>(zbytes);
     w.z[1] = K > 1 ? c.take<char>(zbytes) : nullptr;
     w.partial = c.take<float>((size_t)sched_max_seg(nnz) * (size_t)F);
@@ -410,8 +475,8 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     const int chunks = F / T::kVec;
     E* z_cur = static_cast<E*>(w.z[0]);
     E* z_next = static_cast<E*>(w.z[1]);
-    prescale_rows<T><<<dim3((unsigned)ceil_div((int64_t)n * chunks, kThreads)), dim3(kThreads), 0, stream>>>(
-        static_cast<const E*>(in), ld_in, dinv, z_cur, F, n, F);
+    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kThreads)), dim3(kThreads), 0, stream>>>(
+        static_cast<const E*>(in), ld_in, dinv, z_cur, z_next, n, F);
     E2EG_LAUNCH_CHECK("prescale_rows");
     for (int32_t l = 1; l <= K; ++l) {
         LayerArgs<T> a;
@@ -420,11 +485,9 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
         a.dinv_sqrt = dinv;
         a.sched = view;
         a.zin = z_cur;
-        a.ld_zin = F;
         a.out_h = store[l - 1];
         a.ld_h = ld_store[l - 1];
         a.out_z = l < K ? z_next : nullptr;
-        a.ld_z = F;
         a.addend = add ? add[l - 1] : nullptr;
         a.ld_add = ld_add;
         a.partial = w.partial;
