@@ -19,6 +19,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def recorded_traffic(config: int, scale: float):
+    """HBM bytes per launch of the neighbour-sum kernel from the committed rocprofv3 counter
+    summary, or None when it does not describe the kernel as it is now (sources changed) or
+    this workload."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "spmm_rows_config3.json")
+    if config != 3 or scale != 1.0 or not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    h = hashlib.sha1()
+    for f in ("propagate.hip", "normalize.hip", "common.h"):
+        h.update(open(os.path.join(ROOT, "paper_2511_20564_amd", "csrc", f), "rb").read())
+    return rec["traffic_bytes_per_launch"] if rec.get("source_sha1") == h.hexdigest() else None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -118,7 +133,7 @@ def main():
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": "spmm_rows", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(args.config, args.scale),
         "alg_bytes_per_launch": alg_bytes, "avg_kernel_ms": round(avg_kernel_ms, 4),
         "launches_timed": len(kernel_ms),
         "gather_GBs": round(gather_bytes / (avg_kernel_ms * 1e-3) / 1e9, 1),
