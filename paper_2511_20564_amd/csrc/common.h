@@ -75,46 +75,63 @@ int32_t radix_sort_u64(uint64_t** src, uint64_t** dst, int64_t count, int lo, in
                        hipStream_t stream);
 int bits_for(int64_t count);  // bits needed to represent ids 0 .. count-1 (at least 1)
 
-// ---- schedule layout shared by normalize.hip (writer) and propagate.hip (reader) ----------
-constexpr int kSegLen = 512;       // longest run of CSR entries one wavefront sums
-constexpr int kShortPerWave = 4;   // whole (unsplit) rows a wavefront handles in one go
-constexpr int kWavesPerBlock = 4;  // 256-thread workgroups
+// ---- schedule shared by normalize.hip (writer) and propagate.hip (reader) ------------------
+// The propagation kernels work on a private copy of the graph with renumbered nodes ("internal"
+// ids): the kTopNodes nodes of highest degree come first, by descending degree (ties in node
+// order); all other nodes follow in node order.  Popular nodes, whose feature rows are read most
+// often, so have the lowest ids, sit at the front of every neighbour list, and their feature rows
+// are one contiguous block.
+//
+// Work is cut in two ways.  Rows with at most kShortMax entries ("short") are listed in
+// `short_rows`, ordered by length inside blocks of kSortBlock consecutive rows: a wavefront
+// sums several short rows side by side (one lane group per row), and neighbours in that list
+// have similar lengths.  Longer rows are cut into segments of kSegLen entries, one wavefront
+// each; a row of one segment is finished by that wavefront, a row of several leaves numbered fp32
+// partial sums ("slots") that are added in slot order afterwards.
+constexpr int kShortMax = 128;         // longest row summed by a single lane group
+constexpr int kSegLen = 512;           // longest run of CSR entries summed by one wavefront
+constexpr int kSortBlock = 4096;       // short rows are ordered by length within such blocks
+constexpr int kHotBytes = 128 * 1024;  // feature rows of the most popular nodes kept in LDS
+constexpr int kTopNodes = kHotBytes / 16;  // most rows that can be staged (16-byte rows)
 
-struct alignas(16) WorkItem {
-    int32_t row;   // < 0: padding, nothing to do
-    int32_t beg;   // first CSR entry
-    int32_t end;   // one past the last CSR entry
-    int32_t slot;  // partial-sum slot, or -1 when the item is a whole row
+struct alignas(16) Segment {
+    int32_t row;   // internal row
+    int32_t beg;   // first entry in zcol
+    int32_t end;   // one past the last entry
+    int32_t slot;  // partial-sum slot, or -1 when the segment is the whole row
 };
 
 struct SchedHeader {
-    int32_t n_short;  // rows with at most kSegLen entries (one work item each)
-    int32_t n_seg;    // segments of the longer rows (= partial-sum slots)
-    int32_t n_split;  // rows cut into segments
-    int32_t seg_len;
+    int32_t n_short;  // rows with at most kShortMax entries
+    int32_t n_long;   // rows with more
+    int32_t n_seg;    // segments of those rows
+    int32_t n_multi;  // rows with more than kSegLen entries (several segments)
+    int32_t n_slot;   // segments of those rows (= partial-sum slots)
+    int32_t n_seg_multi;  // = n_slot: the first n_slot entries of `segs` are the slotted ones
     int32_t n;
     int32_t nnz;
-    int32_t pad[2];
 };
 
 struct SchedView {
     SchedHeader* header;
-    WorkItem* seg_items;    // [max_seg_pos] segments of long rows, placed for L2 locality; padded
-    WorkItem* short_items;  // [n] whole rows in node order
-    int32_t* split_row;     // [max_split]
-    int32_t* split_base;    // [max_split] first slot
-    int32_t* split_cnt;     // [max_split] number of slots
-    int64_t max_seg, max_seg_pos, max_split;
+    int32_t* orig;        // [n] node at internal position p
+    int32_t* zpos;        // [n] internal position of node i
+    int32_t* zrow_ptr;    // [n + 1] row pointers of the internal CSR
+    int32_t* zcol;        // [nnz] internal column ids, ascending within each row
+    int32_t* short_rows;  // [n] internal rows with at most kShortMax entries, processing order
+    int32_t* long_row;    // [max_long] internal rows with more than kShortMax entries, ascending
+    int32_t* seg_base;    // [max_long + 1] first segment number of each long row
+    int32_t* multi_row;   // [max_multi] internal rows with more than kSegLen entries, ascending
+    int32_t* slot_base;   // [max_multi + 1] first slot of each such row; [n_multi] = n_slot
+    Segment* segs;        // [max_seg]: slotted segments ordered by first column, then one-segment rows
+    int64_t max_long, max_seg, max_multi, max_slot;
 };
 
-// Upper bounds that depend on (n, nnz) only, so that launches need no device read-back.
-inline int64_t sched_max_split(int64_t nnz) { return nnz / kSegLen + 1; }
-inline int64_t sched_max_seg(int64_t nnz) { return 2 * (nnz / kSegLen) + 2; }
-// Positions in seg_items: room for the per-XCD rounding of the placement, and a whole number of
-// workgroups, so that every wavefront of the segment part of the grid reads an initialised record.
-inline int64_t sched_max_seg_pos(int64_t nnz) {
-    return (sched_max_seg(nnz) + 64 + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
-}
+// Upper bounds that depend on nnz only, so that launches need no device read-back.
+inline int64_t sched_max_long(int64_t nnz) { return nnz / (kShortMax + 1) + 1; }
+inline int64_t sched_max_seg(int64_t nnz) { return nnz / kSegLen + sched_max_long(nnz) + 1; }
+inline int64_t sched_max_multi(int64_t nnz) { return nnz / (kSegLen + 1) + 1; }
+inline int64_t sched_max_slot(int64_t nnz) { return nnz / kSegLen + sched_max_multi(nnz) + 1; }
 size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view);
 
 }  // namespace e2eg

@@ -1,127 +1,200 @@
-// e2eg_normalize: d~_i = sum_j A~_ij and d~_i^-1/2 (paper: Section 3, "Notation"), and the row
-// schedule for the propagation kernels.
+// e2eg_normalize: d~_i = sum_j A~_ij and d~_i^-1/2 (paper: Section 3, "Notation"), and the
+// private, renumbered copy of the graph that the propagation kernels read.
 //
-// Schedule.  Rows with at most kSegLen entries ("short") are one work item each, kept in node
-// order.  Longer rows (the power-law head: popular items whose neighbour lists sweep most of the
-// user range) are cut into segments of kSegLen entries; each segment is summed by one wavefront
-// into a numbered partial-sum slot and the slots of a row are added in slot order afterwards, so
-// results do not depend on timing.  Segments are ordered by their first column and the ordered
-// list is dealt out so that every XCD (workgroup index mod 8) gets one contiguous eighth of it:
-// segments that read the same stretch of feature rows then run at the same time on the same
-// L2, instead of each popular item streaming the whole feature table through every L2.
+// Renumbering.  The kTopNodes nodes of highest degree get internal ids 0, 1, ... by descending
+// degree (ties in node order); all other nodes follow in node order.  The CSR is rewritten in
+// internal ids, rows in internal order, columns ascending.  What this buys on a power-law
+// user-item graph:
+//   - "is this neighbour popular" is one compare, and the feature rows of the most popular
+//     nodes are one contiguous block (the propagation kernel stages it in LDS);
+//   - every neighbour list starts with its popular entries;
+//   - everything else keeps the caller's node order (users, then items), so at any time the
+//     whole GPU gathers from the same side of the graph and the L2 caches hold one hot set.
+// Rows of at most kShortMax entries are listed ordered by length inside blocks of kSortBlock
+// consecutive rows (the kernel sums several of them side by side, so neighbours in the list should
+// be equally long, while the block-wise order keeps the users-then-items progression).  Longer
+// rows are cut into segments of kSegLen entries; the segments of rows with several are ordered by
+// first column, so that segments which read the same stretch of feature rows can be run at the
+// same time on the same L2 (the kernel deals the ordered list out to the XCDs in contiguous
+// eighths); rows of one segment follow in row order.
+// All of it is integer work: radix sorts and scans.  Nothing here depends on the feature width.
 #include "common.h"
 
 namespace e2eg {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kXcds = 8;
 
-__global__ void row_stats(const int32_t* __restrict__ row_ptr, int64_t n,
-                          int32_t* __restrict__ deg, float* __restrict__ dinv_sqrt,
-                          int32_t* __restrict__ is_short, int32_t* __restrict__ slot_cnt,
-                          int32_t* __restrict__ is_split) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n) return;
-    if (i == n) {  // terminators so that the scans deliver the totals at index n
-        is_short[i] = 0;
-        slot_cnt[i] = 0;
-        is_split[i] = 0;
-        return;
-    }
+// Per node: degree, d^-1/2, and the sort key (larger degree first, then node id).
+__global__ void row_stats(const int32_t* __restrict__ row_ptr, int64_t n, int32_t* __restrict__ deg,
+                          float* __restrict__ dinv_sqrt, uint64_t* __restrict__ keys) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
     const int32_t d = row_ptr[i + 1] - row_ptr[i];
     if (deg) deg[i] = d;
     dinv_sqrt[i] = d > 0 ? (float)(1.0 / sqrt((double)d)) : 0.0f;
-    const bool split = d > kSegLen;
-    is_short[i] = split ? 0 : 1;
-    slot_cnt[i] = split ? (d + kSegLen - 1) / kSegLen : 0;
-    is_split[i] = split ? 1 : 0;
+    keys[i] = ((uint64_t)(uint32_t)(0x7fffffff - d) << 32) | (uint32_t)i;
 }
 
-__global__ void fill_padding(WorkItem* __restrict__ items, int64_t count) {
-    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < count) items[k] = WorkItem{-1, 0, 0, -1};
-}
-
-__global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
-    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < count) keys[k] = ~0ull;  // sorts behind every real segment
-}
-
-// One thread per row: short rows become work items; long rows are listed with their slot range.
-__global__ void emit_rows(const int32_t* __restrict__ row_ptr, int64_t n, int64_t nnz,
-                          const int32_t* __restrict__ short_off,
-                          const int32_t* __restrict__ slot_off,
-                          const int32_t* __restrict__ split_idx, SchedView s) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n) return;
-    if (i == n) {
-        SchedHeader h;
-        h.n_short = short_off[n];
-        h.n_seg = slot_off[n];
-        h.n_split = split_idx[n];
-        h.seg_len = kSegLen;
-        h.n = (int32_t)n;
-        h.nnz = (int32_t)nnz;
-        h.pad[0] = h.pad[1] = 0;
-        *s.header = h;
+// Sorted (degree, node) keys -> is the node one of the kTopNodes most popular, and its rank.
+__global__ void mark_top(const uint64_t* __restrict__ sorted, int64_t n, int32_t* __restrict__ rank_of,
+                         int32_t* __restrict__ not_top) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > n) return;
+    if (p == n) {
+        not_top[p] = 0;
         return;
     }
-    const int32_t beg = row_ptr[i], end = row_ptr[i + 1];
-    const int32_t d = end - beg;
-    if (d <= kSegLen) {
-        s.short_items[short_off[i]] = WorkItem{(int32_t)i, beg, end, -1};
-    } else {
-        const int32_t k = split_idx[i];
-        s.split_row[k] = (int32_t)i;
-        s.split_base[k] = slot_off[i];
-        s.split_cnt[k] = (d + kSegLen - 1) / kSegLen;
+    const int32_t i = (int32_t)(uint32_t)sorted[p];
+    rank_of[i] = (int32_t)p;
+    not_top[i] = p < kTopNodes ? 0 : 1;
+}
+
+// others_before = exclusive scan of not_top over node ids.  Internal position: top nodes by
+// rank, the others behind them in node order.  Also per internal row: its length, how it is cut,
+// and the key that orders the short rows (block of kSortBlock rows, then length, then row).
+__global__ void permute_nodes(const int32_t* __restrict__ rank_of, const int32_t* __restrict__ others_before,
+                              const int32_t* __restrict__ row_ptr, int64_t n, int32_t* __restrict__ orig,
+                              int32_t* __restrict__ zpos, int32_t* __restrict__ zdeg,
+                              int32_t* __restrict__ nseg, int32_t* __restrict__ nslot,
+                              int32_t* __restrict__ is_long, int32_t* __restrict__ is_multi,
+                              uint64_t* __restrict__ short_keys) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n) return;
+    if (i == n) {  // terminators so that the scans deliver the totals at index n
+        zdeg[i] = 0;
+        nseg[i] = 0;
+        nslot[i] = 0;
+        is_long[i] = 0;
+        is_multi[i] = 0;
+        return;
+    }
+    const int32_t n_top = n < kTopNodes ? (int32_t)n : kTopNodes;
+    const int32_t r = rank_of[i];
+    const int32_t p = r < kTopNodes ? r : n_top + others_before[i];
+    const int32_t d = row_ptr[i + 1] - row_ptr[i];
+    const int32_t segs = (d + kSegLen - 1) / kSegLen;
+    orig[p] = (int32_t)i;
+    zpos[i] = p;
+    zdeg[p] = d;
+    nseg[p] = d > kShortMax ? segs : 0;
+    nslot[p] = d > kSegLen ? segs : 0;
+    is_long[p] = d > kShortMax ? 1 : 0;
+    is_multi[p] = d > kSegLen ? 1 : 0;
+    const uint32_t hi = d > kShortMax ? 0x7fffffffu : (((uint32_t)p / kSortBlock) << 8) | (uint32_t)d;
+    short_keys[p] = ((uint64_t)hi << 32) | (uint32_t)p;
+}
+
+struct RowScans {          // exclusive scans over internal rows, n + 1 entries each
+    const int32_t* seg_off;
+    const int32_t* slot_off;
+    const int32_t* long_off;
+    const int32_t* multi_off;
+};
+
+__global__ void emit_long_rows(const int32_t* __restrict__ zrow_ptr, RowScans sc, int64_t n, int64_t nnz,
+                               SchedView s) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > n) return;
+    if (p == n) {
+        SchedHeader h;
+        h.n_long = sc.long_off[n];
+        h.n_short = (int32_t)n - h.n_long;
+        h.n_seg = sc.seg_off[n];
+        h.n_multi = sc.multi_off[n];
+        h.n_slot = sc.slot_off[n];
+        h.n_seg_multi = h.n_slot;
+        h.n = (int32_t)n;
+        h.nnz = (int32_t)nnz;
+        *s.header = h;
+        s.seg_base[h.n_long] = h.n_seg;
+        s.slot_base[h.n_multi] = h.n_slot;
+        return;
+    }
+    const int32_t d = zrow_ptr[p + 1] - zrow_ptr[p];
+    if (d > kShortMax) {
+        const int32_t k = sc.long_off[p];  // < max_long: each such row has > kShortMax entries
+        s.long_row[k] = (int32_t)p;
+        s.seg_base[k] = sc.seg_off[p];
+    }
+    if (d > kSegLen) {
+        const int32_t m = sc.multi_off[p];
+        s.multi_row[m] = (int32_t)p;
+        s.slot_base[m] = sc.slot_off[p];
     }
 }
 
-// One thread per segment slot t: find its row (binary search in the ascending slot bases),
-// describe the segment, and key it by its first column for the ordering pass.
-__global__ void emit_segments(const int32_t* __restrict__ row_ptr,
-                              const int32_t* __restrict__ col_idx, SchedView s,
-                              WorkItem* __restrict__ seg_tmp, uint64_t* __restrict__ keys) {
+// One thread per segment t: find its row (binary search in the ascending segment bases),
+// describe the segment, and key it for the ordering pass: slotted segments by first column, then
+// the one-segment rows in row order.
+__global__ void emit_segments(SchedView s, const int32_t* __restrict__ slot_off,
+                              Segment* __restrict__ seg_tmp, uint64_t* __restrict__ keys) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int32_t n_seg = s.header->n_seg;
     if (t >= n_seg) return;
-    int32_t lo = 0, hi = s.header->n_split - 1;  // last k with split_base[k] <= t
+    int32_t lo = 0, hi = s.header->n_long - 1;  // last k with seg_base[k] <= t
     while (lo < hi) {
         const int32_t mid = (lo + hi + 1) >> 1;
-        if (s.split_base[mid] <= t) lo = mid; else hi = mid - 1;
+        if (s.seg_base[mid] <= t) lo = mid; else hi = mid - 1;
     }
-    const int32_t row = s.split_row[lo];
-    const int32_t q = (int32_t)t - s.split_base[lo];
-    const int32_t beg = row_ptr[row] + q * kSegLen;
-    const int32_t row_end = row_ptr[row + 1];
+    const int32_t row = s.long_row[lo];
+    const int32_t q = (int32_t)t - s.seg_base[lo];
+    const int32_t row_beg = s.zrow_ptr[row], row_end = s.zrow_ptr[row + 1];
+    const int32_t beg = row_beg + q * kSegLen;
     const int32_t end = beg + kSegLen < row_end ? beg + kSegLen : row_end;
-    seg_tmp[t] = WorkItem{row, beg, end, (int32_t)t};
-    keys[t] = ((uint64_t)(uint32_t)col_idx[beg] << 32) | (uint32_t)t;
+    const bool multi = row_end - row_beg > kSegLen;
+    seg_tmp[t] = Segment{row, beg, end, multi ? slot_off[row] + q : -1};
+    keys[t] = multi ? ((uint64_t)(uint32_t)s.zcol[beg] << 32) | (uint32_t)t
+                    : (1ull << 63) | ((uint64_t)(uint32_t)t << 32) | (uint32_t)t;
 }
 
-// Ordered position p -> place in seg_items such that XCD x (workgroup index mod 8) owns the
-// x-th contiguous eighth of the ordered list.
-__global__ void place_segments(const uint64_t* __restrict__ keys,
-                               const WorkItem* __restrict__ seg_tmp, SchedView s) {
+__global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) keys[k] = ~0ull;  // sorts behind every real segment
+}
+
+__global__ void place_segments(const uint64_t* __restrict__ keys, const Segment* __restrict__ seg_tmp,
+                               SchedView s) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int32_t n_seg = s.header->n_seg;
-    if (p >= n_seg) return;
-    int64_t per = (n_seg + kXcds - 1) / kXcds;
-    per = (per + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
-    const int64_t xcd = p / per, r = p % per;
-    const int64_t pos = ((r / kWavesPerBlock) * kXcds + xcd) * kWavesPerBlock + r % kWavesPerBlock;
-    s.seg_items[pos] = seg_tmp[(uint32_t)keys[p]];
+    if (p < s.header->n_seg) s.segs[p] = seg_tmp[(uint32_t)keys[p]];
+}
+
+__global__ void place_short_rows(const uint64_t* __restrict__ keys, int64_t n, SchedView s) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) s.short_rows[k] = (int32_t)(uint32_t)keys[k];  // the first n_short are the short rows
+}
+
+// One thread per CSR entry e: key = (internal row << bits) | internal column.
+__global__ void entry_keys(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                           const int32_t* __restrict__ zpos, int64_t n, int64_t nnz, int bits,
+                           uint64_t* __restrict__ keys) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    int64_t lo = 0, hi = n - 1;  // last i with row_ptr[i] <= e
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    keys[e] = ((uint64_t)(uint32_t)zpos[lo] << bits) | (uint32_t)zpos[col_idx[e]];
+}
+
+__global__ void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, int bits,
+                               int32_t* __restrict__ zcol) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < nnz) zcol[e] = (int32_t)(keys[e] & ((1ull << bits) - 1));
 }
 
 struct NormWs {
-    int32_t* is_short;
-    int32_t* slot_cnt;
-    int32_t* is_split;
-    WorkItem* seg_tmp;
     uint64_t* keys_a;
     uint64_t* keys_b;
+    int32_t* rank_of;
+    int32_t* not_top;
+    int32_t* zdeg;
+    int32_t* nseg;
+    int32_t* nslot;
+    int32_t* is_long;
+    int32_t* is_multi;
+    Segment* seg_tmp;
     void* scan_ws;
     void* sort_ws;
     size_t bytes;
@@ -130,15 +203,20 @@ struct NormWs {
 NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     Carver c(base);
     NormWs w;
-    const int64_t max_seg = sched_max_seg(nnz);
-    w.is_short = c.take<int32_t>(n + 1);
-    w.slot_cnt = c.take<int32_t>(n + 1);
-    w.is_split = c.take<int32_t>(n + 1);
-    w.seg_tmp = c.take<WorkItem>(max_seg);
-    w.keys_a = c.take<uint64_t>(max_seg);
-    w.keys_b = c.take<uint64_t>(max_seg);
+    int64_t m = n + 1 > nnz ? n + 1 : nnz;
+    if (sched_max_seg(nnz) > m) m = sched_max_seg(nnz);
+    w.keys_a = c.take<uint64_t>(m);
+    w.keys_b = c.take<uint64_t>(m);
+    w.rank_of = c.take<int32_t>(n + 1);
+    w.not_top = c.take<int32_t>(n + 1);
+    w.zdeg = c.take<int32_t>(n + 1);
+    w.nseg = c.take<int32_t>(n + 1);
+    w.nslot = c.take<int32_t>(n + 1);
+    w.is_long = c.take<int32_t>(n + 1);
+    w.is_multi = c.take<int32_t>(n + 1);
+    w.seg_tmp = c.take<Segment>(sched_max_seg(nnz));
     w.scan_ws = c.take<char>(scan_workspace_bytes(n + 1));
-    w.sort_ws = c.take<char>(radix_sort_workspace_bytes(max_seg));
+    w.sort_ws = c.take<char>(radix_sort_workspace_bytes(m));
     w.bytes = c.size();
     return w;
 }
@@ -181,26 +259,62 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
     SchedView view;
     sched_carve(d_sched, n, nnz, &view);
     const dim3 blk(kThreads);
-    row_stats<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(d_row_ptr, n, d_deg, d_dinv_sqrt, w.is_short,
-                                                           w.slot_cnt, w.is_split);
-    E2EG_LAUNCH_CHECK("row_stats");
-    E2EG_HIP_TRY(exclusive_scan_i32(w.is_short, w.is_short, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.slot_cnt, w.slot_cnt, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.is_split, w.is_split, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    fill_padding<<<grid_for(view.max_seg_pos), blk, 0, stream>>>(view.seg_items, view.max_seg_pos);
-    E2EG_LAUNCH_CHECK("fill_padding");
-    fill_keys<<<grid_for(view.max_seg), blk, 0, stream>>>(w.keys_a, view.max_seg);
-    E2EG_LAUNCH_CHECK("fill_keys");
-    emit_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(d_row_ptr, n, nnz, w.is_short, w.slot_cnt,
-                                                           w.is_split, view);
-    E2EG_LAUNCH_CHECK("emit_rows");
-    if (nnz > kSegLen) {  // otherwise no row can be long
-        emit_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(d_row_ptr, d_col_idx, view, w.seg_tmp,
-                                                                  w.keys_a);
+
+    // 1. degrees, d^-1/2, popularity order, internal numbering
+    uint64_t* src = w.keys_a;
+    uint64_t* dst = w.keys_b;
+    if (n > 0) {
+        row_stats<<<grid_for(n), blk, 0, stream>>>(d_row_ptr, n, d_deg, d_dinv_sqrt, src);
+        E2EG_LAUNCH_CHECK("row_stats");
+        int32_t st = radix_sort_u64(&src, &dst, n, 32, 32, w.sort_ws, stream);
+        if (st != E2EG_OK) return st;
+    }
+    mark_top<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(src, n, w.rank_of, w.not_top);
+    E2EG_LAUNCH_CHECK("mark_top");
+    E2EG_HIP_TRY(exclusive_scan_i32(w.not_top, w.not_top, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    src = w.keys_a;
+    dst = w.keys_b;
+    permute_nodes<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(w.rank_of, w.not_top, d_row_ptr, n, view.orig,
+                                                               view.zpos, w.zdeg, w.nseg, w.nslot, w.is_long,
+                                                               w.is_multi, src);
+    E2EG_LAUNCH_CHECK("permute_nodes");
+    if (n > 0) {  // short rows: by block of kSortBlock rows, then by length
+        int32_t st = radix_sort_u64(&src, &dst, n, 32, 32, w.sort_ws, stream);
+        if (st != E2EG_OK) return st;
+        place_short_rows<<<grid_for(n), blk, 0, stream>>>(src, n, view);
+        E2EG_LAUNCH_CHECK("place_short_rows");
+    }
+    E2EG_HIP_TRY(exclusive_scan_i32(w.zdeg, view.zrow_ptr, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    E2EG_HIP_TRY(exclusive_scan_i32(w.nseg, w.nseg, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    E2EG_HIP_TRY(exclusive_scan_i32(w.nslot, w.nslot, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    E2EG_HIP_TRY(exclusive_scan_i32(w.is_long, w.is_long, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    E2EG_HIP_TRY(exclusive_scan_i32(w.is_multi, w.is_multi, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+
+    // 2. the CSR in internal ids
+    if (nnz > 0) {
+        const int bits = bits_for(n);
+        src = w.keys_a;
+        dst = w.keys_b;
+        entry_keys<<<grid_for(nnz), blk, 0, stream>>>(d_row_ptr, d_col_idx, view.zpos, n, nnz, bits, src);
+        E2EG_LAUNCH_CHECK("entry_keys");
+        int32_t st = radix_sort_u64(&src, &dst, nnz, 0, 2 * bits, w.sort_ws, stream);
+        if (st != E2EG_OK) return st;
+        unpack_columns<<<grid_for(nnz), blk, 0, stream>>>(src, nnz, bits, view.zcol);
+        E2EG_LAUNCH_CHECK("unpack_columns");
+    }
+
+    // 3. long rows and their segments
+    const RowScans sc{w.nseg, w.nslot, w.is_long, w.is_multi};
+    emit_long_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(view.zrow_ptr, sc, n, nnz, view);
+    E2EG_LAUNCH_CHECK("emit_long_rows");
+    if (nnz > kShortMax) {  // otherwise no row can be long
+        src = w.keys_a;
+        dst = w.keys_b;
+        fill_keys<<<grid_for(view.max_seg), blk, 0, stream>>>(src, view.max_seg);
+        E2EG_LAUNCH_CHECK("fill_keys");
+        emit_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(view, w.nslot, w.seg_tmp, src);
         E2EG_LAUNCH_CHECK("emit_segments");
-        uint64_t* src = w.keys_a;
-        uint64_t* dst = w.keys_b;
-        int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, bits_for(n), w.sort_ws, stream);
+        int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, 32, w.sort_ws, stream);
         if (st != E2EG_OK) return st;
         place_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(src, w.seg_tmp, view);
         E2EG_LAUNCH_CHECK("place_segments");

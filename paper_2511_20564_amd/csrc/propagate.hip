@@ -11,27 +11,32 @@
 // carries one extra all-zero row (index n): "no neighbour" lanes read it, which keeps the
 // gather loop free of per-lane predicates.
 //
-// Kernel shape (wave64): a group of G = 16-byte-chunks-per-row lanes reads one neighbour row with
-// 16-byte loads, so a wavefront gathers 64/G neighbour rows per load instruction, eight
-// instructions in flight.  Column indices are fetched 64 at a time (one coalesced load) and
-// handed to the groups through cross-lane moves, the next 64 requested before the current
-// gathers are consumed.  Measured on gfx950 the first version of this loop was bound by vector
-// ALU issue, not by memory (about 36 VALU instructions per 16-byte gather, most of them bf16
-// unpacking, fp32 adds and 64-bit address arithmetic), so the loop is built to need few VALU
-// instructions: byte offsets are 32-bit (one v_mad_u32_u24 per gather, scalar base address),
-// there is no per-lane predicate, and bf16 results are packed by v_cvt_pk_bf16_f32.
-// Work items come from the schedule: whole short rows (several per
-// wavefront) and segments of long rows; segments leave fp32 partial sums that a second kernel
-// adds in a fixed order (in double), so there are no floating-point atomics and results are
-// reproducible.
+// Kernel shape (wave64).  The kernels read the renumbered copy of the graph that e2eg_normalize
+// leaves in the schedule ("internal" ids, see common.h); Z buffers are in internal row order, H
+// is written by node id.  A group of G = 16-byte-chunks-per-row lanes reads one neighbour row
+// with 16-byte loads, so one load instruction of a wavefront fetches 64/G neighbour rows; eight
+// such instructions are in flight per lane.  Byte offsets are 32-bit (one v_mad_u32_u24 per
+// gather on a scalar base address) and "no neighbour" lanes read the zero row, so the loop has
+// no per-lane predicate; bf16 results are packed by v_cvt_pk_bf16_f32.
+//   - Rows of more than kShortMax entries: all 64 lanes work on one row (or on one segment of at
+//     most kSegLen entries of it), the 64/G lane groups taking different neighbours; their sums are
+//     added across lanes at the end.  A row of several segments leaves fp32 partial sums that a
+//     second kernel adds in a fixed order (in double): no floating-point atomics, results are
+//     reproducible.
+//   - Short rows: 64/G rows side by side, one lane group per row.  Nothing is summed across
+//     lanes, and the per-row work (bounds, scale, conversion, store) is paid once per 64/G rows;
+//     on a power-law graph most rows are short and this per-row work, not memory, was what bound
+//     the first version of the kernel (vector-ALU issue).
+// Measured on gfx950: the dot-product instruction v_dot2c_f32_bf16 with unit weights adds a
+// bf16 pair in one instruction instead of shift + add per element, but ran slower than the plain
+// sequence, and capping registers for more resident wavefronts cost more in spills than it gained;
+// neither is used.
 #include "common.h"
 
 #include <type_traits>
 
 namespace e2eg {
 namespace {
-
-constexpr int kThreads = 64 * kWavesPerBlock;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -104,24 +109,22 @@ __device__ __forceinline__ void store_one<BF16>(uint16_t* p, float v) { *p = (ui
 // ---- one layer --------------------------------------------------------------------------------
 template <typename T>
 struct LayerArgs {
-    const int32_t* row_ptr;
-    const int32_t* col_idx;
-    const float* dinv_sqrt;
-    SchedView sched;
-    const typename T::elem* zin;  // Z(l) = S H(l), [n + 1][F], row n all zero
-    typename T::elem* out_h;      // H(l+1) or null
+    const float* dinv_sqrt;       // by node id
+    SchedView sched;              // internal graph (see common.h)
+    const typename T::elem* zin;  // Z(l) = S H(l), [n + 1][F] in internal order, row n all zero
+    typename T::elem* out_h;      // H(l+1) by node id, or null
     int64_t ld_h;
-    typename T::elem* out_z;      // Z(l+1) = S H(l+1), [n + 1][F], or null
-    const typename T::elem* addend;  // direct term added to H(l+1) before scaling, or null
+    typename T::elem* out_z;      // Z(l+1) = S H(l+1), [n + 1][F] in internal order, or null
+    const typename T::elem* addend;  // direct term added to H(l+1) before scaling (by node id), or null
     int64_t ld_add;
     float* partial;               // [slots][F] fp32
     int32_t F;
-    int32_t zero_row;             // = n
-    int32_t seg_blocks;           // workgroups that walk seg_items; the rest walk short_items
+    int32_t n;                    // also the index of the zero row
+    int32_t multi_blocks;         // workgroups of grid part 1
+    int32_t single_blocks;        // workgroups of grid part 2; the rest is part 3
 };
 
-// Accumulators of one work item: acc[v] holds this lane's 16-byte chunk as fp32; the NB lane
-// groups hold separate partial sums that are added across groups at the end.
+// Accumulators of one lane: acc[v] holds this lane's 16-byte chunk as fp32.
 template <typename T>
 struct Sum {
     float acc[T::kVec];
@@ -140,7 +143,14 @@ struct Sum {
             acc[6] += __uint_as_float(q.w << 16); acc[7] += __uint_as_float(q.w & 0xffff0000u);
         }
     }
-    // -> out[] = the chunk's total, valid in lanes of group 0
+    // `live` of the U gathered chunks q[0..U) are valid (wave-uniform count)
+    template <int U>
+    __device__ __forceinline__ void add_batch(const uint4 (&q)[U], int live) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < live) add(q[u]);
+    }
+    // -> out[] = the chunk's total over the lane groups, valid in lanes of group 0
     template <int LOG_G>
     __device__ __forceinline__ void total(float (&out)[T::kVec]) {
 #pragma unroll
@@ -153,33 +163,25 @@ struct Sum {
     }
 };
 
-// Per-row finish: h = s * sum (+ addend); store H and/or Z = s * h.
+// Per-row finish: h = s * sum (+ addend); store H (by node id) and/or Z = s * h (internal row).
 template <typename T>
-__device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t row, int32_t col,
-                                           float (&acc)[T::kVec]) {
-    const float s = a.dinv_sqrt[row];
+__device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t zrow, int32_t node, float s,
+                                           int32_t col, float (&acc)[T::kVec]) {
     float h[T::kVec];
 #pragma unroll
     for (int v = 0; v < T::kVec; ++v) h[v] = s * acc[v];
     if (a.addend) {
         float d[T::kVec];
-        load_vec<T>(a.addend + (int64_t)row * a.ld_add + col, d);
+        load_vec<T>(a.addend + (int64_t)node * a.ld_add + col, d);
 #pragma unroll
         for (int v = 0; v < T::kVec; ++v) h[v] += d[v];
     }
-    if (a.out_h) store_vec<T>(a.out_h + (int64_t)row * a.ld_h + col, h);
+    if (a.out_h) store_vec<T>(a.out_h + (int64_t)node * a.ld_h + col, h);
     if (a.out_z) {
 #pragma unroll
         for (int v = 0; v < T::kVec; ++v) h[v] *= s;
-        store_vec<T>(a.out_z + (int64_t)row * a.F + col, h);
+        store_vec<T>(a.out_z + (int64_t)zrow * a.F + col, h);
     }
-}
-
-// First (up to) 64 column indices of a work item, one per lane; the zero row beyond its end.
-template <typename T>
-__device__ __forceinline__ int32_t first_indices(const LayerArgs<T>& a, const WorkItem& w, int lane) {
-    return (w.row >= 0 && lane < w.end - w.beg) ? __builtin_nontemporal_load(a.col_idx + w.beg + lane)
-                                                : a.zero_row;
 }
 
 // 16 bytes of row j at byte offset `lane_off` inside the row.  NARROW: the table is below 4 GiB
@@ -195,19 +197,30 @@ __device__ __forceinline__ uint4 gather16(const LayerArgs<T>& a, int32_t j, uint
     }
 }
 
-// Sums the neighbour rows of one work item and stores the row (or its partial sum).
-// `idx_first` holds the item's first 64 column indices, fetched ahead by the caller.
+constexpr int kInFlight = 8;  // independent 16-byte gathers in flight per lane
+
+// One segment (entries [beg, end) of internal row seg.row, at most kSegLen of them), all 64 lanes
+// on the one row: G lanes per neighbour row, 64/G neighbour rows per load instruction.  Column
+// indices are fetched 64 at a time, one coalesced load, the next 64 requested before the current
+// gathers are consumed.  slot >= 0: the sum goes to that partial-sum slot; slot < 0: the segment is
+// the whole row and the row is finished here.
 template <typename T, int LOG_G, bool NARROW>
-__device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w, const int32_t idx_first,
-                                         const int lane) {
-    constexpr int G = 1 << LOG_G;    // lanes per neighbour row
-    constexpr int NB = 64 >> LOG_G;  // neighbour rows per load instruction
+__device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment seg, const int lane) {
+    constexpr int G = 1 << LOG_G;
+    constexpr int NB = 64 >> LOG_G;
     constexpr int V = T::kVec;
-    constexpr int U = 8;             // independent gathers in flight per lane
+    constexpr int U = kInFlight;
     const int g = lane >> LOG_G;
     const int c = lane & (G - 1);
     const int chunks = a.F / V;
     const uint32_t row_bytes = (uint32_t)a.F * (uint32_t)sizeof(typename T::elem);
+    int32_t node = 0;
+    float s = 0.0f;
+    if (seg.slot < 0) {  // requested now, needed after the gathers
+        node = a.sched.orig[seg.row];
+        s = a.dinv_sqrt[node];
+    }
+    const int32_t idx_first = lane < seg.end - seg.beg ? __builtin_nontemporal_load(a.sched.zcol + seg.beg + lane) : a.n;
 
     for (int cb = 0; cb < chunks; cb += G) {   // more than one pass only for rows wider than 1 KiB
         const int cc = cb + c;
@@ -215,15 +228,14 @@ __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w
         const uint32_t lane_off = active ? (uint32_t)cc * 16u : 0u;
         Sum<T> sum;
         sum.clear();
-
         int32_t idx = idx_first;
-        for (int32_t base = w.beg; base < w.end; base += 64) {
-            const int cnt = w.end - base < 64 ? w.end - base : 64;
-            int32_t idx_next = a.zero_row;  // next 64 indices, requested before this block's gathers
-            if (base + 64 < w.end && lane < w.end - base - 64)
-                idx_next = __builtin_nontemporal_load(a.col_idx + base + 64 + lane);
+        for (int32_t base = seg.beg; base < seg.end; base += 64) {
+            const int cnt = seg.end - base < 64 ? seg.end - base : 64;
+            int32_t idx_next = a.n;
+            if (base + 64 < seg.end && lane < seg.end - base - 64)
+                idx_next = __builtin_nontemporal_load(a.sched.zcol + base + 64 + lane);
             int t = 0;
-            for (; t + U * NB <= cnt; t += U * NB) {
+            for (; t + U * NB <= cnt; t += U * NB) {   // full batches; lanes past the end hold the zero row
                 uint4 q[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
@@ -231,26 +243,23 @@ __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w
 #pragma unroll
                 for (int u = 0; u < U; ++u) sum.add(q[u]);
             }
-            if (t < cnt) {  // last, partial batch: whole load instructions are skipped uniformly,
-                            // lanes past the end inside a kept instruction read the zero row
+            if (t < cnt) {
                 const int live = (cnt - t + NB - 1) / NB;
                 uint4 q[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
                     if (u < live) q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (u < live) sum.add(q[u]);
+                sum.template add_batch<U>(q, live);
             }
             idx = idx_next;
         }
         float tot[V];
         sum.template total<LOG_G>(tot);
         if (g == 0 && active) {
-            if (w.slot < 0) {
-                finish_vec<T>(a, w.row, cc * V, tot);
+            if (seg.slot < 0) {
+                finish_vec<T>(a, seg.row, node, s, cc * V, tot);
             } else {
-                float* p = a.partial + (int64_t)w.slot * a.F + cc * V;
+                float* p = a.partial + (int64_t)seg.slot * a.F + cc * V;
 #pragma unroll
                 for (int v = 0; v < V; v += 4) {
                     const f32x4 o = {tot[v], tot[v + 1], tot[v + 2], tot[v + 3]};
@@ -261,48 +270,151 @@ __device__ __forceinline__ void run_item(const LayerArgs<T>& a, const WorkItem w
     }
 }
 
-// Workgroups [0, seg_blocks): one segment of a long row per wavefront (placed per XCD by the
-// schedule).  Workgroups beyond: kShortPerWave whole rows per wavefront, the next row's column
-// indices requested while the current row's gathers are in flight.
+// NB = 64/G short rows side by side, lane group g on row g: no sum across lanes is needed and
+// every per-row step (bounds, scale, store) is paid once per NB rows.  Each lane group fetches G
+// of its row's column indices per load (one per lane) and hands them round with cross-lane
+// moves; groups whose row has ended gather the zero row.  `beg`, `len`, `zrow`, `node`, `s` are
+// per-lane values, equal within a lane group; len < 0 for a group without a row (an empty row,
+// len = 0, still gets its all-zero result stored).
 template <typename T, int LOG_G, bool NARROW>
-__global__ __launch_bounds__(kThreads) void spmm_rows(const LayerArgs<T> a) {
+__device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int32_t beg, const int32_t len,
+                                               const int32_t zrow, const int32_t node, const float s,
+                                               const int32_t idx_first, const int lane) {
+    constexpr int G = 1 << LOG_G;
+    constexpr int V = T::kVec;
+    constexpr int U = kInFlight < G ? kInFlight : G;
+    const int c = lane & (G - 1);
+    const int group_base = lane & ~(G - 1);
+    const int chunks = a.F / V;
+    const uint32_t row_bytes = (uint32_t)a.F * (uint32_t)sizeof(typename T::elem);
+    int maxlen = len;  // longest row of the batch (wave-uniform)
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1) {
+        const int o = __shfl_xor(maxlen, off);
+        maxlen = o > maxlen ? o : maxlen;
+    }
+    maxlen = __builtin_amdgcn_readfirstlane(maxlen);
+
+    for (int cb = 0; cb < chunks; cb += G) {
+        const int cc = cb + c;
+        const bool active = cc < chunks;
+        const uint32_t lane_off = active ? (uint32_t)cc * 16u : 0u;
+        Sum<T> sum;
+        sum.clear();
+        int32_t idx = idx_first;
+        for (int base = 0; base < maxlen; base += G) {
+            int32_t idx_next = a.n;
+            if (base + G + c < len) idx_next = __builtin_nontemporal_load(a.sched.zcol + beg + base + G + c);
+            const int steps = maxlen - base < G ? maxlen - base : G;
+            for (int t = 0; t < steps; t += U) {
+                const int live = steps - t < U ? steps - t : U;
+                uint4 q[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (u < live) q[u] = gather16<T, NARROW>(a, __shfl(idx, group_base + t + u), row_bytes, lane_off);
+                sum.template add_batch<U>(q, live);
+            }
+            idx = idx_next;
+        }
+        if (active && len >= 0) finish_vec<T>(a, zrow, node, s, cc * V, sum.acc);
+    }
+}
+
+constexpr int kWaves = 4;          // wavefronts per workgroup
+constexpr int kSegsPerWave = 2;    // segments a wavefront works through
+constexpr int kShortPerWave = 16;  // short rows a wavefront works through, 64/G at a time
+constexpr int kXcds = 8;
+
+// The grid has three parts.
+// 1. Segments of rows cut into several (the first n_slot entries of the ordered segment list,
+//    ordered by first column).  The list is dealt out in contiguous eighths: workgroups x, x+8,
+//    x+16, ... (which the dispatcher places on the same XCD) walk eighth x front to back, so that
+//    segments reading the same stretch of feature rows run at the same time on the same L2.
+// 2. Rows of one segment, in row order.
+// 3. Short rows, kShortPerWave consecutive entries of the ordered short-row list per wavefront.
+//    The wavefront fetches row numbers, bounds, node ids and scales of all its rows up front
+//    (lane i holds row i's) and requests the next batch's first column indices before it works on
+//    the current batch, so that no chain of dependent loads sits between batches.
+template <typename T, int LOG_G, bool NARROW>
+__global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
+    constexpr int G = 1 << LOG_G;
+    constexpr int NB = 64 >> LOG_G;
+    constexpr int kPerBlock = kWaves * kSegsPerWave;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if ((int32_t)blockIdx.x < a.seg_blocks) {
-        const WorkItem w = a.sched.seg_items[(int64_t)blockIdx.x * kWavesPerBlock + wave];
-        if (w.row < 0) return;
-        run_item<T, LOG_G, NARROW>(a, w, first_indices<T>(a, w, lane), lane);
+    if ((int32_t)blockIdx.x < a.multi_blocks) {
+        const int64_t n_slot = a.sched.header->n_slot;
+        int64_t per = (n_slot + kXcds - 1) / kXcds;
+        per = (per + kPerBlock - 1) / kPerBlock * kPerBlock;
+        const int64_t x = blockIdx.x % kXcds;
+        const int64_t first = x * per + (int64_t)(blockIdx.x / kXcds) * kPerBlock + (int64_t)wave * kSegsPerWave;
+        const int64_t limit = (x + 1) * per < n_slot ? (x + 1) * per : n_slot;
+#pragma unroll 1
+        for (int k = 0; k < kSegsPerWave; ++k) {
+            if (first + k >= limit) return;
+            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[first + k], lane);
+        }
         return;
     }
-    const int64_t first = (((int64_t)blockIdx.x - a.seg_blocks) * kWavesPerBlock + wave) * kShortPerWave;
-    const int32_t n_short = a.sched.header->n_short;
+    if ((int32_t)blockIdx.x < a.multi_blocks + a.single_blocks) {
+        const int64_t first = a.sched.header->n_slot +
+                              (((int64_t)blockIdx.x - a.multi_blocks) * kWaves + wave) * kSegsPerWave;
+        const int64_t limit = a.sched.header->n_seg;
+#pragma unroll 1
+        for (int k = 0; k < kSegsPerWave; ++k) {
+            if (first + k >= limit) return;
+            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[first + k], lane);
+        }
+        return;
+    }
+    const int32_t rb = (int32_t)blockIdx.x - a.multi_blocks - a.single_blocks;
+    const int64_t n_short = a.sched.header->n_short;
+    const int64_t first = ((int64_t)rb * kWaves + wave) * kShortPerWave;
     if (first >= n_short) return;
-    WorkItem w[kShortPerWave];
-#pragma unroll
-    for (int r = 0; r < kShortPerWave; ++r)
-        w[r] = first + r < n_short ? a.sched.short_items[first + r] : WorkItem{-1, 0, 0, -1};
-    int32_t idx_cur = first_indices<T>(a, w[0], lane);
-#pragma unroll
-    for (int r = 0; r < kShortPerWave; ++r) {
-        int32_t idx_nxt = a.zero_row;
-        if (r + 1 < kShortPerWave) idx_nxt = first_indices<T>(a, w[r + 1], lane);
-        if (w[r].row >= 0) run_item<T, LOG_G, NARROW>(a, w[r], idx_cur, lane);
+    const int n_rows = n_short - first < kShortPerWave ? (int)(n_short - first) : kShortPerWave;
+    int32_t my_row = 0, my_beg = 0, my_len = -1, my_node = 0;
+    float my_s = 0.0f;
+    if (lane < n_rows) {
+        my_row = a.sched.short_rows[first + lane];
+        my_beg = a.sched.zrow_ptr[my_row];
+        my_len = a.sched.zrow_ptr[my_row + 1] - my_beg;
+        my_node = a.sched.orig[my_row];
+        my_s = a.dinv_sqrt[my_node];
+    }
+    const int c = lane & (G - 1);
+    const int g = lane >> LOG_G;
+    int32_t beg = __shfl(my_beg, g), len = __shfl(my_len, g);
+    int32_t idx_cur = c < len ? __builtin_nontemporal_load(a.sched.zcol + beg + c) : a.n;
+#pragma unroll 1
+    for (int r0 = 0; r0 < n_rows; r0 += NB) {
+        const int src = r0 + g;      // the row of this lane's group (lanes >= n_rows hold len -1)
+        const int nxt = (src + NB) & 63;
+        const int32_t nbeg = __shfl(my_beg, nxt);
+        const int32_t nlen = r0 + NB < n_rows ? __shfl(my_len, nxt) : -1;
+        const int32_t idx_nxt = c < nlen ? __builtin_nontemporal_load(a.sched.zcol + nbeg + c) : a.n;
+        run_short_rows<T, LOG_G, NARROW>(a, beg, len, __shfl(my_row, src), __shfl(my_node, src), __shfl(my_s, src),
+                                         idx_cur, lane);
+        beg = nbeg;
+        len = nlen;
         idx_cur = idx_nxt;
     }
 }
 
-// Rows cut into segments: add their partial sums in a fixed order.  One workgroup per row;
+constexpr int kReduceThreads = 256;
+
+// Rows cut into segments: add their partial sums in a fixed order.  One workgroup per long row;
 // thread (sl, cv) sums slots sl, sl+SL, ... of column quad cv in double, then the SL lane sums
 // are added in lane order.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void reduce_split_rows(const LayerArgs<T> a) {
+__global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerArgs<T> a) {
+    constexpr int kThreads = kReduceThreads;
     __shared__ double red[kThreads][4];
-    const int32_t k = blockIdx.x;
-    if (k >= a.sched.header->n_split) return;
-    const int32_t row = a.sched.split_row[k];
-    const int32_t base = a.sched.split_base[k];
-    const int32_t cnt = a.sched.split_cnt[k];
-    const float s = a.dinv_sqrt[row];
+    if ((int32_t)blockIdx.x >= a.sched.header->n_multi) return;
+    const int32_t k = a.sched.multi_row[blockIdx.x];  // internal row
+    const int32_t node = a.sched.orig[k];
+    const int32_t base = a.sched.slot_base[blockIdx.x];
+    const int32_t cnt = a.sched.slot_base[blockIdx.x + 1] - base;
+    const float s = a.dinv_sqrt[node];
     const int quads = a.F / 4;
     for (int q0 = 0; q0 < quads; q0 += kThreads) {
         const int width = quads - q0 < kThreads ? quads - q0 : kThreads;
@@ -340,48 +452,52 @@ __global__ __launch_bounds__(kThreads) void reduce_split_rows(const LayerArgs<T>
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float h = s * (float)sum[e];
-                if (a.addend) h += load_one<T>(a.addend + (int64_t)row * a.ld_add + col + e);
-                if (a.out_h) store_one<T>(a.out_h + (int64_t)row * a.ld_h + col + e, h);
-                if (a.out_z) store_one<T>(a.out_z + (int64_t)row * a.F + col + e, s * h);
+                if (a.addend) h += load_one<T>(a.addend + (int64_t)node * a.ld_add + col + e);
+                if (a.out_h) store_one<T>(a.out_h + (int64_t)node * a.ld_h + col + e, h);
+                if (a.out_z) store_one<T>(a.out_z + (int64_t)k * a.F + col + e, s * h);
             }
         }
         __syncthreads();
     }
 }
 
-// Z(0) = S X(0): one streaming pass, 16 bytes per thread.  Also clears the zero rows (index n)
-// of both Z buffers.
+constexpr int kPrescaleThreads = 256;
+
+// Z(0) = S X(0) in internal row order: one streaming pass, 16 bytes per thread.  Also clears the
+// zero rows (index n) of both Z buffers.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void prescale_rows(const typename T::elem* __restrict__ x,
-                                                          int64_t ldx,
-                                                          const float* __restrict__ dinv_sqrt,
-                                                          typename T::elem* __restrict__ z,
-                                                          typename T::elem* __restrict__ z_other,
-                                                          int64_t n, int32_t F) {
+__global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename T::elem* __restrict__ x,
+                                                                   int64_t ldx,
+                                                                   const float* __restrict__ dinv_sqrt,
+                                                                   const int32_t* __restrict__ orig,
+                                                                   typename T::elem* __restrict__ z,
+                                                                   typename T::elem* __restrict__ z_other,
+                                                                   int64_t n, int32_t F) {
     constexpr int V = T::kVec;
     const int chunks = F / V;
-    const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t id = (int64_t)blockIdx.x * kPrescaleThreads + threadIdx.x;
     if (id >= (n + 1) * chunks) return;
-    const int64_t row = id / chunks;
-    const int col = (int)(id - row * chunks) * V;
+    const int64_t zrow = id / chunks;
+    const int col = (int)(id - zrow * chunks) * V;
     float v[V];
-    if (row == n) {
+    if (zrow == n) {
 #pragma unroll
         for (int k = 0; k < V; ++k) v[k] = 0.0f;
-        store_vec<T>(z + row * F + col, v);
-        if (z_other) store_vec<T>(z_other + row * F + col, v);
+        store_vec<T>(z + zrow * F + col, v);
+        if (z_other) store_vec<T>(z_other + zrow * F + col, v);
         return;
     }
-    load_vec<T>(x + row * ldx + col, v);
-    const float s = dinv_sqrt[row];
+    const int64_t node = orig[zrow];
+    load_vec<T>(x + node * ldx + col, v);
+    const float s = dinv_sqrt[node];
 #pragma unroll
     for (int k = 0; k < V; ++k) v[k] *= s;
-    store_vec<T>(z + row * F + col, v);
+    store_vec<T>(z + zrow * F + col, v);
 }
 
 template <typename T, bool NARROW>
 void launch_spmm(int log_g, dim3 grid, const LayerArgs<T>& a, hipStream_t stream) {
-    const dim3 blk(kThreads);
+    const dim3 blk(64 * kWaves);
     switch (log_g) {
         case 0: spmm_rows<T, 0, NARROW><<<grid, blk, 0, stream>>>(a); break;
         case 1: spmm_rows<T, 1, NARROW><<<grid, blk, 0, stream>>>(a); break;
@@ -398,20 +514,24 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const int chunks = a.F / T::kVec;
     int log_g = 0;
     while ((1 << log_g) < chunks && log_g < 6) ++log_g;
-    const int64_t seg_blocks = nnz > kSegLen ? ceil_div(sched_max_seg_pos(nnz), kWavesPerBlock) : 0;
-    const int64_t short_blocks = ceil_div(n, (int64_t)kWavesPerBlock * kShortPerWave);
-    a.seg_blocks = (int32_t)seg_blocks;
-    a.zero_row = (int32_t)n;
-    const dim3 grid((unsigned)(seg_blocks + short_blocks));
-    const uint64_t table_bytes = (uint64_t)(n + 1) * (uint64_t)a.F * sizeof(typename T::elem);
+    const uint64_t row_bytes = (uint64_t)a.F * sizeof(typename T::elem);
+    const uint64_t table_bytes = (uint64_t)(n + 1) * row_bytes;
     const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
+    const int64_t multi_blocks =
+        nnz > kSegLen ? kXcds * (ceil_div(ceil_div(sched_max_slot(nnz), kXcds), kWaves * kSegsPerWave) + 1) : 0;
+    const int64_t single_blocks = nnz > kShortMax ? ceil_div(sched_max_long(nnz), kWaves * kSegsPerWave) : 0;
+    const int64_t row_blocks = ceil_div(n, kWaves * kShortPerWave);
+    a.multi_blocks = (int32_t)multi_blocks;
+    a.single_blocks = (int32_t)single_blocks;
+    a.n = (int32_t)n;
+    const dim3 grid((unsigned)(multi_blocks + single_blocks + row_blocks));
     profile_mark(stream, false);
     if (narrow) launch_spmm<T, true>(log_g, grid, a, stream);
     else launch_spmm<T, false>(log_g, grid, a, stream);
     profile_mark(stream, true);
     E2EG_LAUNCH_CHECK("spmm_rows");
-    if (nnz > kSegLen) {  // otherwise no row can be long
-        reduce_split_rows<T><<<dim3((unsigned)sched_max_split(nnz)), dim3(kThreads), 0, stream>>>(a);
+    if (nnz > kSegLen) {  // otherwise no row has several segments
+        reduce_split_rows<T><<<dim3((unsigned)sched_max_multi(nnz)), dim3(kReduceThreads), 0, stream>>>(a);
         E2EG_LAUNCH_CHECK("reduce_split_rows");
     }
     return E2EG_OK;
@@ -430,7 +550,7 @@ PropWs carve_prop(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F, 
     const size_t zbytes = (size_t)(n + 1) * (size_t)F * esz;  // one extra all-zero row
     w.z[0] = c.take<char>(zbytes);
     w.z[1] = K > 1 ? c.take<char>(zbytes) : nullptr;
-    w.partial = c.take<float>((size_t)sched_max_seg(nnz) * (size_t)F);
+    w.partial = c.take<float>((size_t)sched_max_slot(nnz) * (size_t)F);
     w.bytes = c.size();
     return w;
 }
@@ -475,13 +595,12 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     const int chunks = F / T::kVec;
     E* z_cur = static_cast<E*>(w.z[0]);
     E* z_next = static_cast<E*>(w.z[1]);
-    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kThreads)), dim3(kThreads), 0, stream>>>(
-        static_cast<const E*>(in), ld_in, dinv, z_cur, z_next, n, F);
+    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kPrescaleThreads)),
+                       dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig, z_cur,
+                                                            z_next, n, F);
     E2EG_LAUNCH_CHECK("prescale_rows");
     for (int32_t l = 1; l <= K; ++l) {
         LayerArgs<T> a;
-        a.row_ptr = row_ptr;
-        a.col_idx = col_idx;
         a.dinv_sqrt = dinv;
         a.sched = view;
         a.zin = z_cur;
