@@ -91,8 +91,16 @@ int bits_for(int64_t count);  // bits needed to represent ids 0 .. count-1 (at l
 constexpr int kShortMax = 128;         // longest row summed by a single lane group
 constexpr int kSegLen = 512;           // longest run of CSR entries summed by one wavefront
 constexpr int kSortBlock = 4096;       // short rows are ordered by length within such blocks
-constexpr int kHotBytes = 128 * 1024;  // feature rows of the most popular nodes kept in LDS
-constexpr int kTopNodes = kHotBytes / 16;  // most rows that can be staged (16-byte rows)
+constexpr int kHotBytes = 128 * 1024;
+constexpr int kTopNodes = kHotBytes / 16;  // nodes renumbered to the front, by descending degree
+// The longest rows ("wide": among the first kMaxWide internal rows, and at least
+// kWideFactor entries per window on average) are cut at the boundaries of windows of kWindow
+// consecutive internal ids before they are cut by length: a segment then reads feature rows of
+// one window only, and segments of the same window, run together, share them in L2.
+constexpr int kWindow = 8192;
+constexpr int kMaxWide = 1024;
+constexpr int kWideFactor = 16;
+constexpr int kXcds = 8;
 
 struct alignas(16) Segment {
     int32_t row;   // internal row
@@ -102,14 +110,16 @@ struct alignas(16) Segment {
 };
 
 struct SchedHeader {
-    int32_t n_short;  // rows with at most kShortMax entries
-    int32_t n_long;   // rows with more
-    int32_t n_seg;    // segments of those rows
-    int32_t n_multi;  // rows with more than kSegLen entries (several segments)
-    int32_t n_slot;   // segments of those rows (= partial-sum slots)
-    int32_t n_seg_multi;  // = n_slot: the first n_slot entries of `segs` are the slotted ones
+    int32_t n_short;   // rows with at most kShortMax entries
+    int32_t n_seg;     // all segments
+    int32_t n_slot;    // segments of rows cut into several = partial-sum slots = the first n_slot of `segs`
+    int32_t n_multi;   // rows cut into several segments
     int32_t n;
     int32_t nnz;
+    int32_t pad[2];
+    int32_t xcd_first[kXcds + 1];  // the slotted segments dealt out by equal entry counts: XCD x
+                                   // owns segs[xcd_first[x] .. xcd_first[x + 1])
+    int32_t pad2[7];
 };
 
 struct SchedView {
@@ -119,19 +129,27 @@ struct SchedView {
     int32_t* zrow_ptr;    // [n + 1] row pointers of the internal CSR
     int32_t* zcol;        // [nnz] internal column ids, ascending within each row
     int32_t* short_rows;  // [n] internal rows with at most kShortMax entries, processing order
-    int32_t* long_row;    // [max_long] internal rows with more than kShortMax entries, ascending
-    int32_t* seg_base;    // [max_long + 1] first segment number of each long row
-    int32_t* multi_row;   // [max_multi] internal rows with more than kSegLen entries, ascending
-    int32_t* slot_base;   // [max_multi + 1] first slot of each such row; [n_multi] = n_slot
+    int32_t* multi_row;   // [max_multi] internal rows cut into several segments, ascending
+    int32_t* slot_base;   // [max_multi] first slot of each such row
+    int32_t* slot_cnt;    // [max_multi] number of slots
     Segment* segs;        // [max_seg]: slotted segments ordered by first column, then one-segment rows
-    int64_t max_long, max_seg, max_multi, max_slot;
+    int64_t max_plain, max_seg, max_multi, max_slot;
 };
 
-// Upper bounds that depend on nnz only, so that launches need no device read-back.
-inline int64_t sched_max_long(int64_t nnz) { return nnz / (kShortMax + 1) + 1; }
-inline int64_t sched_max_seg(int64_t nnz) { return nnz / kSegLen + sched_max_long(nnz) + 1; }
+// Upper bounds that depend on (n, nnz) only, so that launches need no device read-back.
+inline int64_t sched_windows(int64_t n) { return (n + kWindow - 1) / kWindow; }
+inline int64_t sched_wide_threshold(int64_t n) {
+    const int64_t t = (int64_t)kWideFactor * sched_windows(n);
+    return t > kSegLen ? t : kSegLen + 1;
+}
+inline int64_t sched_max_wide_rows(int64_t n) { return n < kMaxWide ? n : kMaxWide; }
+inline int64_t sched_max_pairs(int64_t n) { return sched_max_wide_rows(n) * sched_windows(n); }
+inline int64_t sched_max_plain(int64_t nnz) { return nnz / (kShortMax + 1) + 1; }  // rows cut by length only
 inline int64_t sched_max_multi(int64_t nnz) { return nnz / (kSegLen + 1) + 1; }
-inline int64_t sched_max_slot(int64_t nnz) { return nnz / kSegLen + sched_max_multi(nnz) + 1; }
+inline int64_t sched_max_slot(int64_t n, int64_t nnz) {
+    return nnz / kSegLen + sched_max_multi(nnz) + sched_max_pairs(n) + 1;
+}
+inline int64_t sched_max_seg(int64_t n, int64_t nnz) { return sched_max_slot(n, nnz) + sched_max_plain(nnz); }
 size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view);
 
 }  // namespace e2eg

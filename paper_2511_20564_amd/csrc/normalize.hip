@@ -50,22 +50,26 @@ __global__ void mark_top(const uint64_t* __restrict__ sorted, int64_t n, int32_t
     not_top[i] = p < kTopNodes ? 0 : 1;
 }
 
+// Row classes by length d:  short d <= kShortMax;  plain kShortMax < d, cut by length only (one
+// segment if d <= kSegLen);  wide: one of the first kMaxWide internal rows with d >= wide_min,
+// cut at window boundaries first.  Rows with d > kSegLen ("multi") leave partial sums.
+//
 // others_before = exclusive scan of not_top over node ids.  Internal position: top nodes by
 // rank, the others behind them in node order.  Also per internal row: its length, how it is cut,
 // and the key that orders the short rows (block of kSortBlock rows, then length, then row).
 __global__ void permute_nodes(const int32_t* __restrict__ rank_of, const int32_t* __restrict__ others_before,
-                              const int32_t* __restrict__ row_ptr, int64_t n, int32_t* __restrict__ orig,
-                              int32_t* __restrict__ zpos, int32_t* __restrict__ zdeg,
-                              int32_t* __restrict__ nseg, int32_t* __restrict__ nslot,
-                              int32_t* __restrict__ is_long, int32_t* __restrict__ is_multi,
-                              uint64_t* __restrict__ short_keys) {
+                              const int32_t* __restrict__ row_ptr, int64_t n, int32_t wide_min,
+                              int32_t* __restrict__ orig, int32_t* __restrict__ zpos,
+                              int32_t* __restrict__ zdeg, int32_t* __restrict__ nseg,
+                              int32_t* __restrict__ nslot, int32_t* __restrict__ is_short,
+                              int32_t* __restrict__ is_multi, uint64_t* __restrict__ short_keys) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i > n) return;
     if (i == n) {  // terminators so that the scans deliver the totals at index n
         zdeg[i] = 0;
         nseg[i] = 0;
         nslot[i] = 0;
-        is_long[i] = 0;
+        is_short[i] = 0;
         is_multi[i] = 0;
         return;
     }
@@ -74,78 +78,143 @@ __global__ void permute_nodes(const int32_t* __restrict__ rank_of, const int32_t
     const int32_t p = r < kTopNodes ? r : n_top + others_before[i];
     const int32_t d = row_ptr[i + 1] - row_ptr[i];
     const int32_t segs = (d + kSegLen - 1) / kSegLen;
+    const bool wide = p < kMaxWide && d >= wide_min;
     orig[p] = (int32_t)i;
     zpos[i] = p;
     zdeg[p] = d;
-    nseg[p] = d > kShortMax ? segs : 0;
-    nslot[p] = d > kSegLen ? segs : 0;
-    is_long[p] = d > kShortMax ? 1 : 0;
+    nseg[p] = (d > kShortMax && !wide) ? segs : 0;   // segments made by cutting by length
+    nslot[p] = (d > kSegLen && !wide) ? segs : 0;    // those of them that are partial-sum slots
+    is_short[p] = d <= kShortMax ? 1 : 0;
     is_multi[p] = d > kSegLen ? 1 : 0;
     const uint32_t hi = d > kShortMax ? 0x7fffffffu : (((uint32_t)p / kSortBlock) << 8) | (uint32_t)d;
     short_keys[p] = ((uint64_t)hi << 32) | (uint32_t)p;
 }
 
+// Wide rows, one thread per (row p, window boundary w), w = 0 .. nwin: position of the first entry
+// of row p with column >= w * kWindow.  Rows that are not wide get an empty range everywhere.
+__global__ void wide_bounds(SchedView s, int32_t wide_rows, int32_t nwin, int32_t wide_min,
+                            int32_t* __restrict__ bounds) {
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= (int64_t)wide_rows * (nwin + 1)) return;
+    const int32_t p = (int32_t)(id / (nwin + 1));
+    const int32_t w = (int32_t)(id - (int64_t)p * (nwin + 1));
+    const int32_t beg = s.zrow_ptr[p], end = s.zrow_ptr[p + 1];
+    if (end - beg < wide_min) {
+        bounds[id] = beg;
+        return;
+    }
+    const int64_t key = (int64_t)w * kWindow;
+    int32_t lo = beg, hi = end;  // first position with zcol >= key
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (s.zcol[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    bounds[id] = lo;
+}
+
+// One thread per (wide row, window): segments needed for its run of entries.
+__global__ void wide_counts(int32_t wide_rows, int32_t nwin, const int32_t* __restrict__ bounds,
+                            int32_t* __restrict__ pair_nseg) {
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t pairs = (int64_t)wide_rows * nwin;
+    if (id > pairs) return;
+    if (id == pairs) {
+        pair_nseg[id] = 0;
+        return;
+    }
+    const int32_t p = (int32_t)(id / nwin);
+    const int32_t w = (int32_t)(id - (int64_t)p * nwin);
+    const int32_t cnt = bounds[(int64_t)p * (nwin + 1) + w + 1] - bounds[(int64_t)p * (nwin + 1) + w];
+    pair_nseg[id] = (cnt + kSegLen - 1) / kSegLen;
+}
+
 struct RowScans {          // exclusive scans over internal rows, n + 1 entries each
     const int32_t* seg_off;
     const int32_t* slot_off;
-    const int32_t* long_off;
+    const int32_t* short_off;
     const int32_t* multi_off;
 };
 
-__global__ void emit_long_rows(const int32_t* __restrict__ zrow_ptr, RowScans sc, int64_t n, int64_t nnz,
-                               SchedView s) {
+// Header and the list of rows that leave partial sums.  pair_off = exclusive scan of pair_nseg.
+__global__ void emit_rows(RowScans sc, const int32_t* __restrict__ pair_off, int32_t wide_rows, int32_t nwin,
+                          int32_t wide_min, int64_t n, int64_t nnz, SchedView s) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > n) return;
+    const int32_t n_slot_plain = sc.slot_off[n];
+    const int32_t n_wide_slots = wide_rows > 0 ? pair_off[(int64_t)wide_rows * nwin] : 0;
     if (p == n) {
         SchedHeader h;
-        h.n_long = sc.long_off[n];
-        h.n_short = (int32_t)n - h.n_long;
-        h.n_seg = sc.seg_off[n];
+        h.n_short = sc.short_off[n];
+        h.n_seg = sc.seg_off[n] + n_wide_slots;
+        h.n_slot = n_slot_plain + n_wide_slots;
         h.n_multi = sc.multi_off[n];
-        h.n_slot = sc.slot_off[n];
-        h.n_seg_multi = h.n_slot;
         h.n = (int32_t)n;
         h.nnz = (int32_t)nnz;
+        h.pad[0] = h.pad[1] = 0;
+        for (int x = 0; x <= kXcds; ++x) h.xcd_first[x] = h.n_slot;  // lowered by deal_segments
+        for (int x = 0; x < 7; ++x) h.pad2[x] = 0;
         *s.header = h;
-        s.seg_base[h.n_long] = h.n_seg;
-        s.slot_base[h.n_multi] = h.n_slot;
         return;
     }
-    const int32_t d = zrow_ptr[p + 1] - zrow_ptr[p];
-    if (d > kShortMax) {
-        const int32_t k = sc.long_off[p];  // < max_long: each such row has > kShortMax entries
-        s.long_row[k] = (int32_t)p;
-        s.seg_base[k] = sc.seg_off[p];
-    }
+    const int32_t d = s.zrow_ptr[p + 1] - s.zrow_ptr[p];
     if (d > kSegLen) {
         const int32_t m = sc.multi_off[p];
         s.multi_row[m] = (int32_t)p;
-        s.slot_base[m] = sc.slot_off[p];
+        if (p < wide_rows && d >= wide_min) {
+            s.slot_base[m] = n_slot_plain + pair_off[(int64_t)p * nwin];
+            s.slot_cnt[m] = pair_off[(int64_t)(p + 1) * nwin] - pair_off[(int64_t)p * nwin];
+        } else {
+            s.slot_base[m] = sc.slot_off[p];
+            s.slot_cnt[m] = (d + kSegLen - 1) / kSegLen;
+        }
     }
 }
 
-// One thread per segment t: find its row (binary search in the ascending segment bases),
-// describe the segment, and key it for the ordering pass: slotted segments by first column, then
-// the one-segment rows in row order.
-__global__ void emit_segments(SchedView s, const int32_t* __restrict__ slot_off,
-                              Segment* __restrict__ seg_tmp, uint64_t* __restrict__ keys) {
+// Sort key of a segment: slotted segments by first column, then the one-segment rows in order.
+__device__ __forceinline__ uint64_t segment_key(const SchedView& s, const Segment& g, int32_t t) {
+    return g.slot >= 0 ? ((uint64_t)(uint32_t)s.zcol[g.beg] << 32) | (uint32_t)t
+                       : (1ull << 63) | ((uint64_t)(uint32_t)t << 32) | (uint32_t)t;
+}
+
+// Segments of rows cut by length only.  One thread per segment t: find its row (binary search in
+// seg_off, the ascending first segment number of every row; rows without such segments repeat
+// their successor's number and are skipped by taking the last row whose number is <= t).
+__global__ void emit_plain_segments(SchedView s, RowScans sc, int64_t n, Segment* __restrict__ seg_tmp,
+                                    uint64_t* __restrict__ keys) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int32_t n_seg = s.header->n_seg;
-    if (t >= n_seg) return;
-    int32_t lo = 0, hi = s.header->n_long - 1;  // last k with seg_base[k] <= t
+    if (t >= sc.seg_off[n]) return;
+    int64_t lo = 0, hi = n - 1;  // last p with seg_off[p] <= t
     while (lo < hi) {
-        const int32_t mid = (lo + hi + 1) >> 1;
-        if (s.seg_base[mid] <= t) lo = mid; else hi = mid - 1;
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (sc.seg_off[mid] <= t) lo = mid; else hi = mid - 1;
     }
-    const int32_t row = s.long_row[lo];
-    const int32_t q = (int32_t)t - s.seg_base[lo];
+    const int32_t row = (int32_t)lo;
+    const int32_t q = (int32_t)t - sc.seg_off[row];
     const int32_t row_beg = s.zrow_ptr[row], row_end = s.zrow_ptr[row + 1];
     const int32_t beg = row_beg + q * kSegLen;
     const int32_t end = beg + kSegLen < row_end ? beg + kSegLen : row_end;
-    const bool multi = row_end - row_beg > kSegLen;
-    seg_tmp[t] = Segment{row, beg, end, multi ? slot_off[row] + q : -1};
-    keys[t] = multi ? ((uint64_t)(uint32_t)s.zcol[beg] << 32) | (uint32_t)t
-                    : (1ull << 63) | ((uint64_t)(uint32_t)t << 32) | (uint32_t)t;
+    const Segment g{row, beg, end, row_end - row_beg > kSegLen ? sc.slot_off[row] + q : -1};
+    seg_tmp[t] = g;
+    keys[t] = segment_key(s, g, (int32_t)t);
+}
+
+// Segments of wide rows: one thread per (row, window) cuts that run by length.
+__global__ void emit_wide_segments(SchedView s, RowScans sc, int64_t n, int32_t wide_rows, int32_t nwin,
+                                   const int32_t* __restrict__ bounds, const int32_t* __restrict__ pair_off,
+                                   Segment* __restrict__ seg_tmp, uint64_t* __restrict__ keys) {
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= (int64_t)wide_rows * nwin) return;
+    const int32_t p = (int32_t)(id / nwin);
+    const int32_t w = (int32_t)(id - (int64_t)p * nwin);
+    const int32_t run_beg = bounds[(int64_t)p * (nwin + 1) + w], run_end = bounds[(int64_t)p * (nwin + 1) + w + 1];
+    const int32_t t0 = sc.seg_off[n] + pair_off[id];        // behind the plain segments
+    const int32_t slot0 = sc.slot_off[n] + pair_off[id];    // behind the plain slots
+    int32_t q = 0;
+    for (int32_t beg = run_beg; beg < run_end; beg += kSegLen, ++q) {
+        const Segment g{p, beg, beg + kSegLen < run_end ? beg + kSegLen : run_end, slot0 + q};
+        seg_tmp[t0 + q] = g;
+        keys[t0 + q] = segment_key(s, g, t0 + q);
+    }
 }
 
 __global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
@@ -153,10 +222,32 @@ __global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
     if (k < count) keys[k] = ~0ull;  // sorts behind every real segment
 }
 
+// Sorted keys -> the ordered segment list, and each slotted segment's length for the deal.
 __global__ void place_segments(const uint64_t* __restrict__ keys, const Segment* __restrict__ seg_tmp,
-                               SchedView s) {
+                               SchedView s, int32_t* __restrict__ seg_len) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < s.header->n_seg) s.segs[p] = seg_tmp[(uint32_t)keys[p]];
+    if (p > s.max_seg) return;
+    int32_t len = 0;
+    if (p < s.header->n_seg) {
+        const Segment g = seg_tmp[(uint32_t)keys[p]];
+        s.segs[p] = g;
+        if (p < s.header->n_slot) len = g.end - g.beg;
+    }
+    seg_len[p] = len;
+}
+
+// len_off = exclusive scan of seg_len (max_seg + 1 entries; the last is the total).  XCD x gets
+// the slotted segments whose running entry count starts in [x, x+1) eighths of the total.
+__global__ void deal_segments(const int32_t* __restrict__ len_off, SchedView s) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t n_slot = s.header->n_slot;
+    if (p >= n_slot) return;
+    const int64_t total = len_off[s.max_seg];
+    const int64_t here = len_off[p], prev = p > 0 ? len_off[p - 1] : -1;
+    for (int x = 0; x < kXcds; ++x) {
+        const int64_t mark = total * x / kXcds;   // first segment whose start count is >= mark
+        if (here >= mark && prev < mark) s.header->xcd_first[x] = (int32_t)p;
+    }
 }
 
 __global__ void place_short_rows(const uint64_t* __restrict__ keys, int64_t n, SchedView s) {
@@ -192,8 +283,11 @@ struct NormWs {
     int32_t* zdeg;
     int32_t* nseg;
     int32_t* nslot;
-    int32_t* is_long;
+    int32_t* is_short;
     int32_t* is_multi;
+    int32_t* bounds;     // [wide rows][windows + 1]
+    int32_t* pair_nseg;  // [wide rows * windows + 1]
+    int32_t* seg_len;    // [max_seg + 1]
     Segment* seg_tmp;
     void* scan_ws;
     void* sort_ws;
@@ -203,8 +297,9 @@ struct NormWs {
 NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     Carver c(base);
     NormWs w;
+    const int64_t max_seg = sched_max_seg(n, nnz);
     int64_t m = n + 1 > nnz ? n + 1 : nnz;
-    if (sched_max_seg(nnz) > m) m = sched_max_seg(nnz);
+    if (max_seg + 1 > m) m = max_seg + 1;
     w.keys_a = c.take<uint64_t>(m);
     w.keys_b = c.take<uint64_t>(m);
     w.rank_of = c.take<int32_t>(n + 1);
@@ -212,10 +307,13 @@ NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     w.zdeg = c.take<int32_t>(n + 1);
     w.nseg = c.take<int32_t>(n + 1);
     w.nslot = c.take<int32_t>(n + 1);
-    w.is_long = c.take<int32_t>(n + 1);
+    w.is_short = c.take<int32_t>(n + 1);
     w.is_multi = c.take<int32_t>(n + 1);
-    w.seg_tmp = c.take<Segment>(sched_max_seg(nnz));
-    w.scan_ws = c.take<char>(scan_workspace_bytes(n + 1));
+    w.bounds = c.take<int32_t>(sched_max_wide_rows(n) * (sched_windows(n) + 1) + 1);
+    w.pair_nseg = c.take<int32_t>(sched_max_pairs(n) + 1);
+    w.seg_len = c.take<int32_t>(max_seg + 1);
+    w.seg_tmp = c.take<Segment>(max_seg);
+    w.scan_ws = c.take<char>(scan_workspace_bytes(m));
     w.sort_ws = c.take<char>(radix_sort_workspace_bytes(m));
     w.bytes = c.size();
     return w;
@@ -274,9 +372,12 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
     E2EG_HIP_TRY(exclusive_scan_i32(w.not_top, w.not_top, (int64_t)n + 1, nullptr, w.scan_ws, stream));
     src = w.keys_a;
     dst = w.keys_b;
-    permute_nodes<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(w.rank_of, w.not_top, d_row_ptr, n, view.orig,
-                                                               view.zpos, w.zdeg, w.nseg, w.nslot, w.is_long,
-                                                               w.is_multi, src);
+    const int32_t wide_min = (int32_t)sched_wide_threshold(n);
+    const int32_t wide_rows = (int32_t)sched_max_wide_rows(n);
+    const int32_t nwin = (int32_t)sched_windows(n);
+    permute_nodes<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(w.rank_of, w.not_top, d_row_ptr, n, wide_min,
+                                                               view.orig, view.zpos, w.zdeg, w.nseg, w.nslot,
+                                                               w.is_short, w.is_multi, src);
     E2EG_LAUNCH_CHECK("permute_nodes");
     if (n > 0) {  // short rows: by block of kSortBlock rows, then by length
         int32_t st = radix_sort_u64(&src, &dst, n, 32, 32, w.sort_ws, stream);
@@ -287,7 +388,7 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
     E2EG_HIP_TRY(exclusive_scan_i32(w.zdeg, view.zrow_ptr, (int64_t)n + 1, nullptr, w.scan_ws, stream));
     E2EG_HIP_TRY(exclusive_scan_i32(w.nseg, w.nseg, (int64_t)n + 1, nullptr, w.scan_ws, stream));
     E2EG_HIP_TRY(exclusive_scan_i32(w.nslot, w.nslot, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.is_long, w.is_long, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    E2EG_HIP_TRY(exclusive_scan_i32(w.is_short, w.is_short, (int64_t)n + 1, nullptr, w.scan_ws, stream));
     E2EG_HIP_TRY(exclusive_scan_i32(w.is_multi, w.is_multi, (int64_t)n + 1, nullptr, w.scan_ws, stream));
 
     // 2. the CSR in internal ids
@@ -303,21 +404,38 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
         E2EG_LAUNCH_CHECK("unpack_columns");
     }
 
-    // 3. long rows and their segments
-    const RowScans sc{w.nseg, w.nslot, w.is_long, w.is_multi};
-    emit_long_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(view.zrow_ptr, sc, n, nnz, view);
-    E2EG_LAUNCH_CHECK("emit_long_rows");
+    // 3. segments: wide rows by window then length, the other long rows by length; ordered and dealt
+    const RowScans sc{w.nseg, w.nslot, w.is_short, w.is_multi};
+    const int64_t pairs = (int64_t)wide_rows * nwin;
+    if (pairs > 0) {
+        wide_bounds<<<grid_for((int64_t)wide_rows * (nwin + 1)), blk, 0, stream>>>(view, wide_rows, nwin, wide_min,
+                                                                                  w.bounds);
+        E2EG_LAUNCH_CHECK("wide_bounds");
+        wide_counts<<<grid_for(pairs + 1), blk, 0, stream>>>(wide_rows, nwin, w.bounds, w.pair_nseg);
+        E2EG_LAUNCH_CHECK("wide_counts");
+        E2EG_HIP_TRY(exclusive_scan_i32(w.pair_nseg, w.pair_nseg, pairs + 1, nullptr, w.scan_ws, stream));
+    }
+    emit_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(sc, w.pair_nseg, wide_rows, nwin, wide_min, n, nnz, view);
+    E2EG_LAUNCH_CHECK("emit_rows");
     if (nnz > kShortMax) {  // otherwise no row can be long
         src = w.keys_a;
         dst = w.keys_b;
         fill_keys<<<grid_for(view.max_seg), blk, 0, stream>>>(src, view.max_seg);
         E2EG_LAUNCH_CHECK("fill_keys");
-        emit_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(view, w.nslot, w.seg_tmp, src);
-        E2EG_LAUNCH_CHECK("emit_segments");
+        emit_plain_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(view, sc, n, w.seg_tmp, src);
+        E2EG_LAUNCH_CHECK("emit_plain_segments");
+        if (pairs > 0) {
+            emit_wide_segments<<<grid_for(pairs), blk, 0, stream>>>(view, sc, n, wide_rows, nwin, w.bounds,
+                                                                   w.pair_nseg, w.seg_tmp, src);
+            E2EG_LAUNCH_CHECK("emit_wide_segments");
+        }
         int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, 32, w.sort_ws, stream);
         if (st != E2EG_OK) return st;
-        place_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(src, w.seg_tmp, view);
+        place_segments<<<grid_for(view.max_seg + 1), blk, 0, stream>>>(src, w.seg_tmp, view, w.seg_len);
         E2EG_LAUNCH_CHECK("place_segments");
+        E2EG_HIP_TRY(exclusive_scan_i32(w.seg_len, w.seg_len, view.max_seg + 1, nullptr, w.scan_ws, stream));
+        deal_segments<<<grid_for(view.max_slot + 1), blk, 0, stream>>>(w.seg_len, view);
+        E2EG_LAUNCH_CHECK("deal_segments");
     }
     return E2EG_OK;
 }

@@ -120,8 +120,8 @@ struct LayerArgs {
     float* partial;               // [slots][F] fp32
     int32_t F;
     int32_t n;                    // also the index of the zero row
-    int32_t multi_blocks;         // workgroups of grid part 1
-    int32_t single_blocks;        // workgroups of grid part 2; the rest is part 3
+    int32_t a_blocks;             // workgroups per XCD the launch provides for slotted segments
+    int32_t b_blocks;             // workgroups per XCD for rows of one segment
 };
 
 // Accumulators of one lane: acc[v] holds this lane's 16-byte chunk as fp32.
@@ -321,53 +321,62 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
 }
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
-constexpr int kSegsPerWave = 2;    // segments a wavefront works through
 constexpr int kShortPerWave = 16;  // short rows a wavefront works through, 64/G at a time
-constexpr int kXcds = 8;
+constexpr int kSingleBlocksPerXcd = 512;
 
-// The grid has three parts.
-// 1. Segments of rows cut into several (the first n_slot entries of the ordered segment list,
-//    ordered by first column).  The list is dealt out in contiguous eighths: workgroups x, x+8,
-//    x+16, ... (which the dispatcher places on the same XCD) walk eighth x front to back, so that
-//    segments reading the same stretch of feature rows run at the same time on the same L2.
-// 2. Rows of one segment, in row order.
-// 3. Short rows, kShortPerWave consecutive entries of the ordered short-row list per wavefront.
+// Three kinds of workgroup.
+// A. Segments of rows cut into several (the first n_slot entries of the ordered segment list,
+//    ordered by first column), one per wavefront.  The schedule deals the list out to the XCDs in
+//    contiguous stretches of equal entry counts; the A-workgroups of XCD x take the segments of
+//    stretch x in order, so the segments in flight on an XCD are consecutive ones, read the same
+//    window of feature rows, and share it in that XCD's L2.  (Should a stretch be longer than
+//    the launch was sized for, the workgroups go round again.)
+// B. Rows of one segment, in row order; a fixed number of workgroups with equal shares.
+// C. Short rows, kShortPerWave consecutive entries of the ordered short-row list per wavefront.
 //    The wavefront fetches row numbers, bounds, node ids and scales of all its rows up front
 //    (lane i holds row i's) and requests the next batch's first column indices before it works on
 //    the current batch, so that no chain of dependent loads sits between batches.
+// Workgroup b runs on XCD b mod 8 and XCDs take their workgroups in index order: on each XCD
+// the sequence is its A-workgroups, then its share of B, then of C.  How many workgroups of each
+// kind there really are is read from the schedule; the launch is sized for upper bounds and the
+// workgroups beyond the real ones, all at the end of each XCD's sequence, leave at once.
+// (Measured: spreading the L2-bound A-workgroups evenly among the HBM-bound others, so that both
+// resources are busy all the time, was slower than running them one after the other.)
 template <typename T, int LOG_G, bool NARROW>
 __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
-    constexpr int kPerBlock = kWaves * kSegsPerWave;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if ((int32_t)blockIdx.x < a.multi_blocks) {
-        const int64_t n_slot = a.sched.header->n_slot;
-        int64_t per = (n_slot + kXcds - 1) / kXcds;
-        per = (per + kPerBlock - 1) / kPerBlock * kPerBlock;
-        const int64_t x = blockIdx.x % kXcds;
-        const int64_t first = x * per + (int64_t)(blockIdx.x / kXcds) * kPerBlock + (int64_t)wave * kSegsPerWave;
-        const int64_t limit = (x + 1) * per < n_slot ? (x + 1) * per : n_slot;
+    const SchedHeader* h = a.sched.header;
+    const int x = blockIdx.x % kXcds;
+    const int64_t j = blockIdx.x / kXcds;   // position in this XCD's sequence
+    const int64_t a_lo = h->xcd_first[x], a_hi = h->xcd_first[x + 1];
+    int64_t n_a = (a_hi - a_lo + kWaves - 1) / kWaves;
+    if (n_a > a.a_blocks) n_a = a.a_blocks;   // a longer stretch than the launch was sized for: go round again
+    const int64_t c_total = ((int64_t)h->n_short + kWaves * kShortPerWave - 1) / (kWaves * kShortPerWave);
+    const int64_t n_b = a.b_blocks;                      // a fixed number, with equal shares of the rows
+    const int64_t n_c = (c_total + kXcds - 1 - x) / kXcds;
+    const int64_t total = n_a + n_b + n_c;
+    if (j >= total) return;
+    if (j < n_a) {
 #pragma unroll 1
-        for (int k = 0; k < kSegsPerWave; ++k) {
-            if (first + k >= limit) return;
-            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[first + k], lane);
-        }
+        for (int64_t t = a_lo + j * kWaves + wave; t < a_hi; t += n_a * kWaves)
+            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[t], lane);
         return;
     }
-    if ((int32_t)blockIdx.x < a.multi_blocks + a.single_blocks) {
-        const int64_t first = a.sched.header->n_slot +
-                              (((int64_t)blockIdx.x - a.multi_blocks) * kWaves + wave) * kSegsPerWave;
-        const int64_t limit = a.sched.header->n_seg;
+    const int64_t o = j - n_a;                           // position among the B- and C-workgroups
+    if (o < n_b) {
+        const int64_t lo = h->n_slot, hi = h->n_seg;
+        const int64_t waves = n_b * kXcds * kWaves;
+        const int64_t per_wave = (hi - lo + waves - 1) / waves;
+        const int64_t first = lo + ((o * kXcds + x) * kWaves + wave) * per_wave;
+        const int64_t last = first + per_wave < hi ? first + per_wave : hi;
 #pragma unroll 1
-        for (int k = 0; k < kSegsPerWave; ++k) {
-            if (first + k >= limit) return;
-            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[first + k], lane);
-        }
+        for (int64_t t = first; t < last; ++t) run_segment<T, LOG_G, NARROW>(a, a.sched.segs[t], lane);
         return;
     }
-    const int32_t rb = (int32_t)blockIdx.x - a.multi_blocks - a.single_blocks;
+    const int64_t rb = (o - n_b) * kXcds + x;
     const int64_t n_short = a.sched.header->n_short;
     const int64_t first = ((int64_t)rb * kWaves + wave) * kShortPerWave;
     if (first >= n_short) return;
@@ -413,7 +422,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
     const int32_t k = a.sched.multi_row[blockIdx.x];  // internal row
     const int32_t node = a.sched.orig[k];
     const int32_t base = a.sched.slot_base[blockIdx.x];
-    const int32_t cnt = a.sched.slot_base[blockIdx.x + 1] - base;
+    const int32_t cnt = a.sched.slot_cnt[blockIdx.x];
     const float s = a.dinv_sqrt[node];
     const int quads = a.F / 4;
     for (int q0 = 0; q0 < quads; q0 += kThreads) {
@@ -517,14 +526,14 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const uint64_t row_bytes = (uint64_t)a.F * sizeof(typename T::elem);
     const uint64_t table_bytes = (uint64_t)(n + 1) * row_bytes;
     const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
-    const int64_t multi_blocks =
-        nnz > kSegLen ? kXcds * (ceil_div(ceil_div(sched_max_slot(nnz), kXcds), kWaves * kSegsPerWave) + 1) : 0;
-    const int64_t single_blocks = nnz > kShortMax ? ceil_div(sched_max_long(nnz), kWaves * kSegsPerWave) : 0;
-    const int64_t row_blocks = ceil_div(n, kWaves * kShortPerWave);
-    a.multi_blocks = (int32_t)multi_blocks;
-    a.single_blocks = (int32_t)single_blocks;
+    // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs
+    const int64_t a_blocks = nnz > kSegLen ? ceil_div(ceil_div(sched_max_slot(n, nnz), kWaves), kXcds) + 1 : 0;
+    const int64_t b_blocks = nnz > kShortMax ? kSingleBlocksPerXcd : 0;
+    const int64_t c_blocks = ceil_div(ceil_div(n, kWaves * kShortPerWave), kXcds) + 1;
     a.n = (int32_t)n;
-    const dim3 grid((unsigned)(multi_blocks + single_blocks + row_blocks));
+    a.a_blocks = (int32_t)a_blocks;
+    a.b_blocks = (int32_t)b_blocks;
+    const dim3 grid((unsigned)(kXcds * (a_blocks + b_blocks + c_blocks)));
     profile_mark(stream, false);
     if (narrow) launch_spmm<T, true>(log_g, grid, a, stream);
     else launch_spmm<T, false>(log_g, grid, a, stream);
@@ -550,7 +559,7 @@ PropWs carve_prop(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F, 
     const size_t zbytes = (size_t)(n + 1) * (size_t)F * esz;  // one extra all-zero row
     w.z[0] = c.take<char>(zbytes);
     w.z[1] = K > 1 ? c.take<char>(zbytes) : nullptr;
-    w.partial = c.take<float>((size_t)sched_max_slot(nnz) * (size_t)F);
+    w.partial = c.take<float>((size_t)sched_max_slot(n, nnz) * (size_t)F);
     w.bytes = c.size();
     return w;
 }

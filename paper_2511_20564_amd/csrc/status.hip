@@ -52,20 +52,19 @@ int32_t fail(int32_t status, const char* fmt, ...) {
 size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view) {
     Carver c(base);
     SchedView v;
-    v.max_long = sched_max_long(nnz);
-    v.max_seg = sched_max_seg(nnz);
+    v.max_plain = sched_max_plain(nnz);
+    v.max_seg = sched_max_seg(n, nnz);
     v.max_multi = sched_max_multi(nnz);
-    v.max_slot = sched_max_slot(nnz);
+    v.max_slot = sched_max_slot(n, nnz);
     v.header = c.take<SchedHeader>(1);
     v.orig = c.take<int32_t>(n > 0 ? n : 1);
     v.zpos = c.take<int32_t>(n > 0 ? n : 1);
     v.zrow_ptr = c.take<int32_t>(n + 1);
     v.zcol = c.take<int32_t>(nnz > 0 ? nnz : 1);
     v.short_rows = c.take<int32_t>(n > 0 ? n : 1);
-    v.long_row = c.take<int32_t>(v.max_long);
-    v.seg_base = c.take<int32_t>(v.max_long + 1);
     v.multi_row = c.take<int32_t>(v.max_multi);
-    v.slot_base = c.take<int32_t>(v.max_multi + 1);
+    v.slot_base = c.take<int32_t>(v.max_multi);
+    v.slot_cnt = c.take<int32_t>(v.max_multi);
     v.segs = c.take<Segment>(v.max_seg);
     if (view) *view = v;
     return c.size();
