@@ -162,6 +162,12 @@ int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
 int32_t e2eg_profile_begin(int32_t capacity);
 int32_t e2eg_profile_end(float* h_ms, int32_t h_capacity, int32_t* h_count);
 
+/* Measurement aid: a plain streaming copy of nbytes device bytes (a multiple of 16, both pointers
+ * 16-byte aligned, buffers must not overlap), one kernel (copy_bytes16) enqueued on `stream`.  It
+ * reads nbytes and writes nbytes: the traffic of known size against which the profiler's HBM
+ * byte counters are scaled. */
+int32_t e2eg_profile_copy(void* d_dst, const void* d_src, size_t nbytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,7 @@ SIGNATURES = {
     "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "e2eg_profile_begin": (_i32, [_i32]),
     "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
+    "e2eg_profile_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
 }
 
 _lib = None
@@ -173,3 +174,7 @@ def e2eg_profile_end(capacity: int):
     count = _i32(0)
     _check(load_library().e2eg_profile_end(buf, capacity, ctypes.byref(count)))
     return [float(buf[k]) for k in range(min(capacity, count.value))]
+
+
+def e2eg_profile_copy(d_dst, d_src, nbytes: int, stream=0):
+    _check(load_library().e2eg_profile_copy(_ptr(d_dst), _ptr(d_src), nbytes, stream or None))

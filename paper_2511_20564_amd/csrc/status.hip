@@ -72,6 +72,15 @@ size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view) {
 
 }  // namespace e2eg
 
+namespace e2eg {
+// Plain streaming copy, 16 bytes per thread: the traffic of known size against which hardware
+// byte counters are scaled.
+__global__ void copy_bytes16(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t chunks) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < chunks) dst[i] = src[i];
+}
+}  // namespace e2eg
+
 extern "C" {
 
 const char* e2eg_status_string(int32_t status) {
@@ -124,6 +133,18 @@ int32_t e2eg_profile_end(float* h_ms, int32_t h_capacity, int32_t* h_count) {
     p.start.clear();
     p.stop.clear();
     return status;
+}
+
+int32_t e2eg_profile_copy(void* d_dst, const void* d_src, size_t nbytes, void* stream) {
+    if (!d_dst || !d_src) return e2eg::fail(E2EG_ERR_NULL_PTR, "profile_copy: null pointer");
+    if (nbytes % 16 != 0 || !e2eg::aligned_to(d_dst, 16) || !e2eg::aligned_to(d_src, 16))
+        return e2eg::fail(E2EG_ERR_INVALID_ARG, "profile_copy: pointers and size must be multiples of 16 bytes");
+    if (nbytes == 0) return E2EG_OK;
+    const size_t chunks = nbytes / 16;
+    e2eg::copy_bytes16<<<dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<uint4*>(d_dst), static_cast<const uint4*>(d_src), chunks);
+    E2EG_LAUNCH_CHECK("copy_bytes16");
+    return E2EG_OK;
 }
 
 }  // extern "C"

@@ -155,6 +155,8 @@ def test_layer_transform_argument_errors(B):
 
 def test_profile_aid_rejects_bad_arguments(B):
     assert status_of(B, B.e2eg_profile_begin, -1) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_profile_copy, None, None, 16) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, B.e2eg_profile_copy, 4096, 8192, 24) == B.E2EG_ERR_INVALID_ARG
 
 
 def test_device_helpers_refuse_to_run_without_gpu():

@@ -119,6 +119,49 @@ def test_propagate_feature_widths(dev, oracle, dtype, F, K):
     run_case(dev, oracle, c)
 
 
+@pytest.mark.parametrize("dtype,F", [("f32", 8), ("f32", 64), ("f32", 320), ("bf16", 16), ("bf16", 128), ("bf16", 1024)])
+def test_propagate_long_rows_feature_widths(dev, oracle, dtype, F):
+    """Rows of every class at each lane layout: a few items with thousands of neighbours (cut at
+    window boundaries and by length), items and users with 129..512 (one wavefront per row) and
+    short rows, on more nodes than one window holds."""
+    rng = np.random.default_rng(F)
+    nu, ni = 12000, 300
+    deg = np.concatenate([np.full(4, 9000), np.full(40, 700), np.full(60, 300), np.full(ni - 104, 12)])
+    items = np.repeat(np.arange(ni), deg)
+    users = np.concatenate([rng.choice(nu, size=d, replace=False) for d in deg])
+    heavy = rng.choice(nu, size=8, replace=False)             # a few users with 129..300 items
+    hu = np.repeat(heavy, ni)
+    hi = np.tile(np.arange(ni), 8)
+    users = np.concatenate([users, hu]).astype(np.int32)
+    items = np.concatenate([items, hi]).astype(np.int32)
+    n = nu + ni
+    c = dict(n_users=nu, n_items=ni, users=users, items=items, dtype=dtype, K=2,
+             X0=make_features(n, F, 0.1, 1, dtype), gY=make_features(n, F, 1.0, 2, dtype))
+    run_case(dev, oracle, c)
+
+
+def test_propagate_many_tiny_segments(dev, oracle):
+    """A thousand popular items that each have one neighbour in every window of the node range and
+    a dense run in one: the segment list is mostly one-entry segments, all dealt to one XCD, many
+    more than the launch provides workgroups for, so those workgroups go round the list again."""
+    rng = np.random.default_rng(11)
+    nu, ni = 300_000, 1024
+    dense = rng.choice(nu, size=3000, replace=False)
+    wins = nu // 8192
+    u_parts, i_parts = [], []
+    for it in range(ni):
+        spread = (np.arange(1, wins) * 8192 + rng.integers(0, 8192, size=wins - 1)).astype(np.int64)
+        u = np.unique(np.concatenate([dense, spread[spread < nu]]))
+        u_parts.append(u)
+        i_parts.append(np.full(u.size, it))
+    users = np.concatenate(u_parts).astype(np.int32)
+    items = np.concatenate(i_parts).astype(np.int32)
+    n, F = nu + ni, 16
+    c = dict(n_users=nu, n_items=ni, users=users, items=items, dtype="f32", K=2,
+             X0=make_features(n, F, 0.1, 1, "f32"), gY=make_features(n, F, 1.0, 2, "f32"))
+    run_case(dev, oracle, c)
+
+
 def test_propagate_without_self_loops(dev, oracle):
     nu, ni, ne = 50, 400, 900         # leaves many items without neighbours
     users, items = uniform_bipartite(nu, ni, ne, seed=5)
