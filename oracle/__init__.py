@@ -52,6 +52,9 @@ def _load():
         lib.e2eg_oracle_propagate_layer_transposed.argtypes = lib.e2eg_oracle_propagate_layer.argtypes
         lib.e2eg_oracle_propagate_rows.argtypes = [ctypes.c_int64, _i64p, _i64p, _i32p, ctypes.c_int64,
                                                    _f64p, _f64p]
+        lib.e2eg_oracle_readout_mean.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
+        lib.e2eg_oracle_gfae_loss.restype = ctypes.c_double
+        lib.e2eg_oracle_gfae_loss.argtypes = [ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
         lib.e2eg_oracle_transform_fwd.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p,
                                                   ctypes.c_int32, _f64p, _f64p]
         lib.e2eg_oracle_transform_bwd.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p,
@@ -168,15 +171,52 @@ def propagate_fwd(row_ptr, col_idx, X0, K):
     return layers
 
 
-def propagate_bwd(row_ptr, col_idx, gHK, K, g_layers=None):
-    """dL/dH(0) given dL/dH(K) and optional direct terms dL/dH(1..K-1) (list of K-1
-    arrays, entry l-1 for layer l)."""
+def propagate_bwd(row_ptr, col_idx, gHK, K, g_layers=None, g_shared=None):
+    """dL/dH(0) given dL/dH(K) and optional direct terms: `g_layers`, dL/dH(1..K-1) (list of
+    K-1 arrays, entry l-1 for layer l), or `g_shared`, one array that is the direct term of every
+    layer 0..K-1 (a loss that reads all layers with equal weight)."""
     G = as_f64(gHK)
     for l in range(K - 1, -1, -1):
         G = propagate_layer_transposed(row_ptr, col_idx, G)
         if g_layers is not None and l >= 1:
             G = G + as_f64(g_layers[l - 1])
+        if g_shared is not None:
+            G = G + as_f64(g_shared)
     return G
+
+
+def readout_mean(X0, layers):
+    """Y = 1/(K+1) (H(0) + ... + H(K)) with H(0) = X0 and layers = [H(1), ..., H(K)]."""
+    X0 = as_f64(X0)
+    K = len(layers)
+    n, F = X0.shape
+    L = _c(np.stack([as_f64(h) for h in layers]) if K else np.zeros((0, n, F)), np.float64)
+    Y = np.empty_like(X0)
+    _load().e2eg_oracle_readout_mean(n, F, K, _p(X0, _f64p), _p(L, _f64p), _p(Y, _f64p))
+    return Y
+
+
+def gfae_loss(X, Y):
+    """-> (||X - Y||_F^2, dL/dY = 2 (Y - X))."""
+    X = as_f64(X)
+    Y = as_f64(Y)
+    assert X.shape == Y.shape
+    n, F = X.shape
+    gY = np.empty_like(X)
+    loss = _load().e2eg_oracle_gfae_loss(n, F, _p(X, _f64p), _p(Y, _f64p), _p(gY, _f64p))
+    return float(loss), gY
+
+
+def gfae_step(row_ptr, col_idx, X0, K):
+    """The self-supervised branch end to end on a LightGCN encoder: Y = mean of the K+1 layers,
+    L = ||X0 - Y||_F^2, and dL/dX0 through the readout and the K layers (X0 also enters the loss
+    directly).  -> (loss, Y, dL/dX0)."""
+    layers = propagate_fwd(row_ptr, col_idx, X0, K)
+    Y = readout_mean(X0, layers)
+    loss, gY = gfae_loss(X0, Y)
+    g = gY / (K + 1)                      # dL/dH(l), the same for every layer l = 0..K
+    G0 = propagate_bwd(row_ptr, col_idx, g, K, g_shared=g)
+    return loss, Y, G0 - gY               # - gY = 2 (X0 - Y): the direct dependence of the loss on X0
 
 
 def transform_fwd(P, W, relu=True):

@@ -23,6 +23,9 @@
  *     the J^T dL/dF_gnn terms of the multi-task gradient).  Written as a
  *     scatter over the forward CSR so that it is the transpose by construction
  *     and assumes no symmetry.
+ *   - Layer combination of LightGCN, Y = 1/(L+1) sum_{l=0..L} H(l) (Section 3.1, the final
+ *     representation as the mean of all layers), and the GFAE reconstruction loss with the
+ *     identity decoder, L_ssl = ||X - Y||_F^2 (Section 4.2), with dL/dY = 2 (Y - X).
  *   - Dense per-layer update Z = P W, H' = max(Z, 0): the update function psi of
  *     the generic message-passing layer with the W, sigma of the GraphSAGE
  *     layer (Section 3 and Section 3.1), and its backward.
@@ -209,4 +212,31 @@ void e2eg_oracle_transform_bwd(int64_t n, int64_t Fin, int64_t Fout, const doubl
             dW[c * Fout + o] = s;
         }
     free(dZ);
+}
+
+/*
+ * Layer combination (Section 3.1):  Y = 1/(K+1) * (H(0) + H(1) + ... + H(K)).
+ * X0 = H(0) is [n][F]; layers holds H(1..K) back to back, each [n][F].
+ */
+void e2eg_oracle_readout_mean(int64_t n, int64_t F, int64_t K, const double* X0, const double* layers,
+                              double* Y) {
+    for (int64_t k = 0; k < n * F; ++k) {
+        double s = X0[k];
+        for (int64_t l = 0; l < K; ++l) s += layers[l * n * F + k];
+        Y[k] = s / (double)(K + 1);
+    }
+}
+
+/*
+ * GFAE reconstruction loss with the identity decoder (Section 4.2):  L = ||X - Y||_F^2 = sum (X - Y)^2,
+ * returned; if gY is not NULL it receives dL/dY = 2 (Y - X).
+ */
+double e2eg_oracle_gfae_loss(int64_t n, int64_t F, const double* X, const double* Y, double* gY) {
+    double loss = 0.0;
+    for (int64_t k = 0; k < n * F; ++k) {
+        double d = X[k] - Y[k];
+        loss += d * d;
+        if (gY) gY[k] = 2.0 * (Y[k] - X[k]);
+    }
+    return loss;
 }

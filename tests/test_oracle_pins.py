@@ -9,7 +9,9 @@
  * the backward being the transpose (dense A^T G, adjoint identity, finite differences),
    also on a deliberately non-symmetric structure;
  * an independent library evaluation (scipy.sparse);
- * the per-node LightGCN update of Section 3.1 written as python loops (no self-loop variant).
+ * the per-node LightGCN update of Section 3.1 written as python loops (no self-loop variant);
+ * layer-mean readout and GFAE loss: a hand-worked single-edge case (tests/golden/), the dense
+   mean of powers of A^, numpy's Frobenius norm, finite differences of the whole chain.
 """
 import os
 
@@ -472,3 +474,78 @@ def test_transform_finite_differences(oracle):
         Wp[idx] += h
         Wm[idx] -= h
         assert abs((loss(P, Wp) - loss(P, Wm)) / (2 * h) - dW[idx]) < 1e-6
+
+
+# ---------------------------------------------------------------- readout + GFAE loss
+def test_readout_and_gfae_single_edge_golden(oracle):
+    g = _golden("gfae_single_edge.txt")
+    row_ptr, col = oracle.build_csr(1, 1, np.array([0], np.int32), np.array([0], np.int32))
+    X = np.array([[3.0, -1.0], [1.0, 5.0]])
+    loss, Y, gX = oracle.gfae_step(row_ptr, col, X, 2)
+    assert np.allclose(Y, [[g["y_u0"], g["y_u1"]], [g["y_i0"], g["y_i1"]]], rtol=1e-14)
+    assert abs(loss - g["loss"]) < 1e-13
+    _, gY = oracle.gfae_loss(X, Y)
+    assert np.allclose(gY[0], [g["gy_u0"], g["gy_u1"]], rtol=1e-14)
+    assert np.allclose(gX, [[g["gx_u0"], g["gx_u1"]], [g["gx_i0"], g["gx_i1"]]], rtol=1e-13)
+
+
+def test_readout_no_edges_reproduces_input(oracle):
+    row_ptr, col = oracle.build_csr(4, 3, np.zeros(0, np.int32), np.zeros(0, np.int32))
+    X = np.random.default_rng(3).standard_normal((7, 5))
+    loss, Y, gX = oracle.gfae_step(row_ptr, col, X, 3)
+    assert np.array_equal(Y, X) and loss == 0.0 and not gX.any()
+
+
+@pytest.mark.parametrize("seed,K", [(1, 1), (2, 2), (3, 4)])
+def test_readout_and_loss_match_dense(oracle, seed, K):
+    nu, ni, u, i = small_graph(seed)
+    n = nu + ni
+    Ahat, _ = dense_ahat(nu, ni, u, i)
+    X = np.random.default_rng(seed).standard_normal((n, 6))
+    M = sum(np.linalg.matrix_power(Ahat, l) for l in range(K + 1)) / (K + 1)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    loss, Y, gX = oracle.gfae_step(row_ptr, col, X, K)
+    assert relerr(Y, M @ X) < 1e-12
+    assert abs(loss - np.linalg.norm(X - M @ X, "fro") ** 2) <= 1e-12 * loss
+    R = np.eye(n) - M
+    assert relerr(gX, 2.0 * R.T @ (R @ X)) < 1e-11
+    # plausible slips are not within reach of these pins: mean over K instead of K+1, layer 0
+    # left out of the mean, the sign of the gradient, the direct dependence on X forgotten
+    layers = oracle.propagate_fwd(row_ptr, col, X, K)
+    assert relerr(sum(layers) / K, M @ X) > 1e-3
+    assert relerr((X + sum(layers)) / K, M @ X) > 1e-3
+    g = 2.0 * (Y - X) / (K + 1)
+    G0 = oracle.propagate_bwd(row_ptr, col, g, K, g_shared=g)
+    assert relerr(G0, 2.0 * R.T @ (R @ X)) > 1e-3            # without the - gY term
+    assert relerr(-gX, 2.0 * R.T @ (R @ X)) > 1e-3
+
+
+def test_gfae_gradient_finite_differences(oracle):
+    nu, ni, u, i = small_graph(8, nu=6, ni=4, ne=14)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    K = 3
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((nu + ni, 3))
+    _, _, gX = oracle.gfae_step(row_ptr, col, X, K)
+    h = 1e-6
+    for _ in range(12):
+        r, c = rng.integers(0, nu + ni), rng.integers(0, 3)
+        Xp, Xm = X.copy(), X.copy()
+        Xp[r, c] += h
+        Xm[r, c] -= h
+        fd = (oracle.gfae_step(row_ptr, col, Xp, K)[0] - oracle.gfae_step(row_ptr, col, Xm, K)[0]) / (2 * h)
+        assert abs(fd - gX[r, c]) <= 1e-6 * max(1.0, abs(gX[r, c]))
+
+
+def test_shared_direct_terms_equal_explicit_ones(oracle):
+    """propagate_bwd with one shared direct term equals the general form fed K-1 copies, plus
+    the term of layer 0."""
+    nu, ni, u, i = small_graph(4)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    rng = np.random.default_rng(1)
+    g = rng.standard_normal((nu + ni, 4))
+    gK = rng.standard_normal((nu + ni, 4))
+    K = 3
+    a = oracle.propagate_bwd(row_ptr, col, gK, K, g_shared=g)
+    b = oracle.propagate_bwd(row_ptr, col, gK, K, g_layers=[g] * (K - 1)) + g
+    assert relerr(a, b) < 1e-14
