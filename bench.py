@@ -136,6 +136,31 @@ def main():
     fwd_ms = timed(lambda: dev.propagate_fwd(g, X0, K, out=out_f, ws=ws))
     bwd_ms = timed(lambda: dev.propagate_bwd(g, gY, K, out=out_b, ws=ws))
 
+    # the streaming passes of the self-supervised branch (layer-mean readout, reconstruction loss and
+    # its gradient), each timed with events on the stream it runs on; bytes are the algorithmic ones
+    def event_ms(fn, reps=5):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    H_all = dev.propagate_fwd(g, X0, K, all_layers=True)
+    Y = dev.readout_mean(X0, H_all)
+    readout_ms = event_ms(lambda: dev.readout_mean(X0, H_all))
+    loss_ms = event_ms(lambda: dev.gfae_loss(X0, Y, grad_scale=1.0 / (K + 1)))
+    readout_bytes = (K + 2) * n * F * esz
+    loss_bytes = 3 * n * F * esz
+    gfae = {
+        "readout_mean_ms": round(readout_ms, 4), "readout_mean_GBs": round(readout_bytes / readout_ms / 1e6, 1),
+        "gfae_loss_ms": round(loss_ms, 4), "gfae_loss_GBs": round(loss_bytes / loss_ms / 1e6, 1),
+        "hbm_peak_GBs": HBM_PEAK_GBS,
+    }
+    del H_all, Y
+
     # roofline of the neighbour-sum kernel: algorithmic bytes of one layer over its mean duration
     alg_bytes = 4 * nnz + 4 * (n + 1) + 4 * n + 2 * n * F * esz
     gather_bytes = alg_bytes - n * F * esz + nnz * F * esz + 4 * nnz
@@ -183,7 +208,7 @@ def main():
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
         "build_csr_ms": round(build_ms - normalize_ms, 3), "normalize_ms": round(normalize_ms, 3),
         "alg_GBs": round(alg_bytes * 2 * K / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae,
     }
     print(json.dumps(line), flush=True)
 

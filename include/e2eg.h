@@ -120,6 +120,9 @@ int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
  * gradient on layer l (a loss that reads intermediate layers), D(0) = 0; output d_gX0 = G(0).
  * d_gLayers == NULL means no direct terms; else layer l (1 <= l <= K-1) is at
  * d_gLayers + (l-1)*g_layer_stride elements with leading dimension ldg.
+ * g_layer_stride == 0 means ONE array [n][F] (ldg) that is the direct term of every layer
+ * l = 0 .. K-1, layer 0 included: the backward of a loss that reads all layers with equal weight
+ * (the mean readout of e2eg_readout_mean, with d_gXK holding the same array for layer K).
  * The CSR must be structurally symmetric (everything e2eg_build_csr produces is), so that
  * A^T = A^ and the same row schedule serves; this is not checked.
  */
@@ -149,6 +152,35 @@ int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
                              int32_t relu, const void* d_P, const void* d_W, void* d_H,
                              const void* d_gH, void* d_gP, float* d_gW, void* ws,
                              size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_readout_mean: layer combination of LightGCN (Section 3.1): the final representation is
+ * the mean of all layers,  Y = 1/(K+1) * (H(0) + H(1) + ... + H(K)).
+ *
+ * d_X0 = H(0) [n][F] (ldx); d_layers holds H(1..K) as e2eg_propagate_fwd stores them with a
+ * non-zero layer_stride: layer l at d_layers + (l-1)*layer_stride elements, leading dimension ld
+ * (layer_stride is not looked at when K <= 1; d_layers may be NULL when K == 0).  d_Y [n][F] (ldy)
+ * must not overlap the inputs.  fp32 arithmetic, one rounding to the storage type.
+ */
+int32_t e2eg_readout_mean(int32_t n, int32_t dtype, int32_t F, int32_t K, const void* d_X0, int64_t ldx,
+                          const void* d_layers, int64_t ld, int64_t layer_stride, void* d_Y,
+                          int64_t ldy, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * e2eg_gfae_loss: the graph feature auto-encoder loss with the identity decoder (Section 4.2),
+ *     L_ssl = || X - Y ||_F^2 ,
+ * X the input features and Y the encoder output, and its gradient with respect to Y.
+ *
+ * *d_loss (a DEVICE double) receives the loss, summed in double in a fixed order (the value is
+ * reproducible).  If d_gY is not NULL it receives grad_scale * dL/dY = grad_scale * 2 (Y - X) in
+ * the storage type (ldg); grad_scale carries whatever constant factors follow (a task weight,
+ * the 1/(K+1) of the mean readout).  d_gY must not overlap d_X or d_Y.  The gradient with respect
+ * to X itself, when X is a trainable embedding, is the negative of the (unscaled) d_gY.
+ */
+size_t e2eg_gfae_loss_workspace_bytes(int32_t n, int32_t F);
+int32_t e2eg_gfae_loss(int32_t n, int32_t dtype, int32_t F, const void* d_X, int64_t ldx, const void* d_Y,
+                       int64_t ldy, double* d_loss, void* d_gY, int64_t ldg, float grad_scale, void* ws,
+                       size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Measurement aid (not part of the path): per-launch duration of the neighbour-sum kernel, the

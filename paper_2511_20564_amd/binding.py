@@ -43,6 +43,9 @@ SIGNATURES = {
     "e2eg_propagate_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_layer_transform_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "e2eg_readout_mean": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
+    "e2eg_gfae_loss_workspace_bytes": (_sz, [_i32, _i32]),
+    "e2eg_gfae_loss": (_i32, [_i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _sz, _vp]),
     "e2eg_profile_begin": (_i32, [_i32]),
     "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "e2eg_profile_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
@@ -178,3 +181,18 @@ def e2eg_profile_end(capacity: int):
 
 def e2eg_profile_copy(d_dst, d_src, nbytes: int, stream=0):
     _check(load_library().e2eg_profile_copy(_ptr(d_dst), _ptr(d_src), nbytes, stream or None))
+
+
+def e2eg_readout_mean(n, dtype, F, K, d_X0, ldx, d_layers, ld, layer_stride, d_Y, ldy, stream=0):
+    _check(load_library().e2eg_readout_mean(n, dtype, F, K, _ptr(d_X0), ldx, _ptr(d_layers), ld, layer_stride,
+                                            _ptr(d_Y), ldy, stream or None))
+
+
+def e2eg_gfae_loss_workspace_bytes(n, F) -> int:
+    return int(load_library().e2eg_gfae_loss_workspace_bytes(n, F))
+
+
+def e2eg_gfae_loss(n, dtype, F, d_X, ldx, d_Y, ldy, d_loss, d_gY, ldg, grad_scale, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_gfae_loss(n, dtype, F, _ptr(d_X), ldx, _ptr(d_Y), ldy, _ptr(d_loss), _ptr(d_gY), ldg,
+                                         grad_scale, _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                         stream or None))

@@ -696,10 +696,11 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
     if ((st = check_matrix(who, "d_gXK", d_gXK, ldg, F, dtype)) != E2EG_OK) return st;
     if ((st = check_matrix(who, "d_gX0", d_gX0, ldo, F, dtype)) != E2EG_OK) return st;
     const int vec = dtype == E2EG_F32 ? 4 : 8;
-    if (d_gLayers && K > 1) {
+    const bool shared_term = d_gLayers && g_layer_stride == 0;  // one direct term for layers 0..K-1
+    if (d_gLayers && (K > 1 || shared_term)) {
         if (!aligned_to(d_gLayers, 16)) return fail(E2EG_ERR_INVALID_ARG, "%s: d_gLayers is not 16-byte aligned", who);
-        if (g_layer_stride < (int64_t)n * ldg || g_layer_stride % vec != 0)
-            return fail(E2EG_ERR_INVALID_ARG, "%s: g_layer_stride %lld must be >= n*ldg and a multiple of %d",
+        if (!shared_term && (g_layer_stride < (int64_t)n * ldg || g_layer_stride % vec != 0))
+            return fail(E2EG_ERR_INVALID_ARG, "%s: g_layer_stride %lld must be 0 or >= n*ldg and a multiple of %d",
                         who, (long long)g_layer_stride, vec);
     }
     const size_t need = e2eg_propagate_workspace_bytes(n, nnz, dtype, F, K);
@@ -718,7 +719,9 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
         for (int L = 1; L <= K; ++L) {
             const int l = K - L;
             store[L - 1] = L == K ? static_cast<float*>(d_gX0) : nullptr;
-            add[L - 1] = (d_gLayers && l >= 1) ? static_cast<const float*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride : nullptr;
+            add[L - 1] = shared_term ? static_cast<const float*>(d_gLayers)
+                         : (d_gLayers && l >= 1) ? static_cast<const float*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride
+                                                 : nullptr;
         }
         return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
                                lds, add, ldg, w, stream);
@@ -728,7 +731,9 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
     for (int L = 1; L <= K; ++L) {
         const int l = K - L;
         store[L - 1] = L == K ? static_cast<uint16_t*>(d_gX0) : nullptr;
-        add[L - 1] = (d_gLayers && l >= 1) ? static_cast<const uint16_t*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride : nullptr;
+        add[L - 1] = shared_term ? static_cast<const uint16_t*>(d_gLayers)
+                     : (d_gLayers && l >= 1) ? static_cast<const uint16_t*>(d_gLayers) + (int64_t)(l - 1) * g_layer_stride
+                                             : nullptr;
     }
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
                             lds, add, ldg, w, stream);

@@ -100,8 +100,10 @@ def propagate_fwd(g: Graph, X0: torch.Tensor, K: int, all_layers: bool = False, 
 
 
 def propagate_bwd(g: Graph, gXK: torch.Tensor, K: int, g_layers: torch.Tensor | None = None,
-                  out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
-    """dL/dH(0) from dL/dH(K) (and optional direct terms dL/dH(1..K-1) as [K-1, n, F])."""
+                  out: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                  g_shared: torch.Tensor | None = None) -> torch.Tensor:
+    """dL/dH(0) from dL/dH(K) and optional direct terms: `g_layers`, dL/dH(1..K-1) as [K-1, n, F],
+    or `g_shared`, one [n, F] array that is the direct term of every layer 0..K-1."""
     _require_gpu()
     n, F = gXK.shape
     assert n == g.n and gXK.stride(1) == 1
@@ -113,6 +115,9 @@ def propagate_bwd(g: Graph, gXK: torch.Tensor, K: int, g_layers: torch.Tensor | 
     if g_layers is not None:
         assert g_layers.shape == (K - 1, n, F) and g_layers.is_contiguous() and gXK.stride(0) == F
         stride = n * F
+    if g_shared is not None:
+        assert g_layers is None and g_shared.shape == (n, F) and g_shared.is_contiguous() and gXK.stride(0) == F
+        g_layers = g_shared
     B.e2eg_propagate_bwd(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(gXK), F, K,
                          gXK, gXK.stride(0), g_layers, stride, out, F, ws, None, _stream())
     return out
@@ -144,3 +149,27 @@ def layer_transform_bwd(P: torch.Tensor, W: torch.Tensor, H: torch.Tensor, gH: t
     B.e2eg_layer_transform(B.E2EG_TRANSFORM_BWD, n, Fin, Fout, code, int(relu), P, W, H, gH, gP, gW, ws, None,
                            _stream())
     return gP, gW
+
+
+def readout_mean(X0: torch.Tensor, layers: torch.Tensor) -> torch.Tensor:
+    """Y = (X0 + layers[0] + ... + layers[K-1]) / (K + 1); layers is [K, n, F] as propagate_fwd stores it."""
+    _require_gpu()
+    n, F = X0.shape
+    K = layers.shape[0]
+    assert layers.shape == (K, n, F) and layers.is_contiguous() and X0.stride(1) == 1 and layers.dtype == X0.dtype
+    Y = torch.empty((n, F), dtype=X0.dtype, device=X0.device)
+    B.e2eg_readout_mean(n, _dtype_code(X0), F, K, X0, X0.stride(0), layers, F, n * F, Y, F, _stream())
+    return Y
+
+
+def gfae_loss(X: torch.Tensor, Y: torch.Tensor, grad_scale: float = 1.0, want_grad: bool = True):
+    """-> (loss as a 1-element float64 device tensor, grad_scale * 2 (Y - X) or None)."""
+    _require_gpu()
+    n, F = X.shape
+    assert Y.shape == (n, F) and X.stride(1) == 1 and Y.stride(1) == 1 and X.dtype == Y.dtype
+    loss = torch.empty(1, dtype=torch.float64, device=X.device)
+    gY = torch.empty((n, F), dtype=X.dtype, device=X.device) if want_grad else None
+    ws = _bytes(B.e2eg_gfae_loss_workspace_bytes(n, F), X.device)
+    B.e2eg_gfae_loss(n, _dtype_code(X), F, X, X.stride(0), Y, Y.stride(0), loss, gY, F, float(grad_scale), ws, None,
+                     _stream())
+    return loss, gY

@@ -153,6 +153,27 @@ def test_layer_transform_argument_errors(B):
         == B.E2EG_ERR_WORKSPACE
 
 
+def test_readout_and_gfae_argument_errors(B):
+    r = B.e2eg_readout_mean
+    assert status_of(B, r, 10, B.E2EG_F32, 6, 2, FAKE, 6, FAKE, 6, 60, FAKE, 6) == B.E2EG_ERR_INVALID_ARG   # F % 4
+    assert status_of(B, r, 10, 7, 8, 2, FAKE, 8, FAKE, 8, 80, FAKE, 8) == B.E2EG_ERR_BAD_DTYPE
+    assert status_of(B, r, 10, B.E2EG_F32, 8, 2, None, 8, FAKE, 8, 80, FAKE, 8) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, r, 10, B.E2EG_F32, 8, 2, FAKE, 8, None, 8, 80, FAKE, 8) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, r, 10, B.E2EG_F32, 8, 2, FAKE, 8, FAKE, 8, 40, FAKE, 8) == B.E2EG_ERR_INVALID_ARG  # stride < n*ld
+    assert status_of(B, r, 10, B.E2EG_F32, 8, -1, FAKE, 8, FAKE, 8, 80, FAKE, 8) == B.E2EG_ERR_INVALID_ARG
+    r(0, B.E2EG_F32, 8, 0, FAKE, 8, None, 8, 0, FAKE, 8)       # n = 0: nothing to do, nothing launched
+    g = B.e2eg_gfae_loss
+    assert B.e2eg_gfae_loss_workspace_bytes(10, 8) > 0
+    assert status_of(B, g, 10, B.E2EG_BF16, 12, FAKE, 16, FAKE, 16, FAKE, None, 16, 1.0, FAKE, 1 << 20) \
+        == B.E2EG_ERR_INVALID_ARG                             # F % 8
+    assert status_of(B, g, 10, B.E2EG_BF16, 16, FAKE, 16, FAKE, 16, None, None, 16, 1.0, FAKE, 1 << 20) \
+        == B.E2EG_ERR_NULL_PTR                                # no place for the loss
+    assert status_of(B, g, 10, B.E2EG_BF16, 16, FAKE, 16, FAKE, 8, FAKE, None, 16, 1.0, FAKE, 1 << 20) \
+        == B.E2EG_ERR_INVALID_ARG                             # ldy < F
+    assert status_of(B, g, 10, B.E2EG_BF16, 16, FAKE, 16, FAKE, 16, FAKE, None, 16, 1.0, FAKE, 8) \
+        == B.E2EG_ERR_WORKSPACE
+
+
 def test_profile_aid_rejects_bad_arguments(B):
     assert status_of(B, B.e2eg_profile_begin, -1) == B.E2EG_ERR_INVALID_ARG
     assert status_of(B, B.e2eg_profile_copy, None, None, 16) == B.E2EG_ERR_NULL_PTR

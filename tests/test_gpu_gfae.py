@@ -1,0 +1,95 @@
+"""GPU parity of the self-supervised branch on a LightGCN encoder: layer-mean readout, GFAE
+reconstruction loss and its gradient pushed back through the K layers (one shared direct term
+per layer), each stage against the oracle applied to the GPU's own inputs of that stage, and the
+whole chain end to end."""
+import numpy as np
+import pytest
+import torch
+
+from parity import TOL, assert_close, to_device, to_f64
+from workloads import make_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2511_20564_amd.device as d
+    d.B.load_library()
+    return d
+
+
+def bits(t):
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.detach().cpu().numpy()
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (2, 0.2), (3, 0.02)])
+def test_gfae_stages_and_chain(dev, oracle, cfg, scale):
+    c = make_config(cfg, scale=scale)
+    K, dt = c["K"], c["dtype"]
+    tol = TOL[dt]
+    u = torch.from_numpy(c["users"]).cuda()
+    i = torch.from_numpy(c["items"]).cuda()
+    g = dev.build_graph(c["n_users"], c["n_items"], u, i)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    X0 = to_device(c["X0"], dt)
+    H = dev.propagate_fwd(g, X0, K, all_layers=True)
+    Y = dev.readout_mean(X0, H)
+    loss, gY = dev.gfae_loss(X0, Y, grad_scale=1.0 / (K + 1))
+    gH0 = dev.propagate_bwd(g, gY, K, g_shared=gY)
+    torch.cuda.synchronize()
+
+    # readout against the oracle's mean of the GPU's stored layers
+    layers = [oracle.as_f64(bits(H[k])) for k in range(K)]
+    Yr = oracle.readout_mean(c["X0"], layers)
+    Ys = oracle.readout_mean(np.abs(oracle.as_f64(c["X0"])), [np.abs(h) for h in layers])
+    assert_close(to_f64(Y), Yr, Ys, dt, "readout")
+    # loss and gradient against the oracle on the GPU's Y
+    lr, gr = oracle.gfae_loss(c["X0"], bits(Y))
+    assert abs(float(loss.item()) - lr) <= 1e-10 * lr
+    gs = 2.0 * (np.abs(oracle.as_f64(c["X0"])) + np.abs(oracle.as_f64(bits(Y)))) / (K + 1)
+    assert_close(to_f64(gY), gr / (K + 1), gs, dt, "loss gradient")
+    # backward with the shared direct term against the oracle on the GPU's gY
+    Gr = oracle.propagate_bwd(row_ptr, col, bits(gY), K, g_shared=oracle.as_f64(bits(gY)))
+    a = np.abs(oracle.as_f64(bits(gY)))
+    Gs = oracle.propagate_bwd(row_ptr, col, a, K, g_shared=a)
+    assert_close(to_f64(gH0), Gr, Gs, dt, "backward with shared direct term")
+    # end to end against the oracle that never rounds
+    loss_t, Y_t, gX_t = oracle.gfae_step(row_ptr, col, c["X0"], K)
+    assert abs(float(loss.item()) - loss_t) <= 4 * tol * loss_t
+    gX = to_f64(gH0) - (K + 1) * to_f64(gY)              # + 2 (X0 - Y): the loss reads X0 directly
+    drift = np.abs(gX - gX_t).max() / np.abs(gX_t).max()
+    assert drift <= 8 * tol, drift
+
+
+@pytest.mark.parametrize("dtype,F,K", [("f32", 4, 0), ("f32", 20, 1), ("bf16", 8, 3), ("bf16", 264, 2)])
+def test_readout_and_loss_shapes(dev, oracle, dtype, F, K):
+    from workloads import make_features
+    n = 1037
+    X = make_features(n, F, 0.5, 3, dtype)
+    L = [make_features(n, F, 0.5, 10 + k, dtype) for k in range(K)]
+    Xd = to_device(X, dtype)
+    Ld = torch.stack([to_device(l, dtype) for l in L]) if K else torch.empty((0, n, F), dtype=Xd.dtype, device="cuda")
+    Y = dev.readout_mean(Xd, Ld)
+    loss, gY = dev.gfae_loss(Xd, Y, grad_scale=0.5)
+    loss2, none = dev.gfae_loss(Xd, Y, want_grad=False)
+    torch.cuda.synchronize()
+    Yr = oracle.readout_mean(X, L)
+    Ys = oracle.readout_mean(np.abs(oracle.as_f64(X)), [np.abs(oracle.as_f64(l)) for l in L])
+    assert_close(to_f64(Y), Yr, Ys, dtype, "readout")
+    lr, gr = oracle.gfae_loss(X, bits(Y))
+    assert none is None and float(loss.item()) == float(loss2.item())
+    assert abs(float(loss.item()) - lr) <= 1e-10 * max(lr, 1e-300)
+    gs = np.abs(oracle.as_f64(X)) + np.abs(oracle.as_f64(bits(Y)))
+    assert_close(to_f64(gY), 0.5 * gr, gs, dtype, "gradient")
+
+
+def test_loss_is_reproducible(dev):
+    from workloads import make_features
+    X = to_device(make_features(50_000, 64, 1.0, 1, "f32"), "f32")
+    Y = to_device(make_features(50_000, 64, 1.0, 2, "f32"), "f32")
+    a = dev.gfae_loss(X, Y, want_grad=False)[0].item()
+    b = dev.gfae_loss(X, Y, want_grad=False)[0].item()
+    assert a == b
