@@ -160,6 +160,16 @@ def main():
         "hbm_peak_GBs": HBM_PEAK_GBS,
     }
     del H_all, Y
+    # two upstream gradients (one per task, as GradNorm needs them) through the K layers: two passes
+    # of F columns against one pass of 2F columns
+    g2 = torch.cat([gY, X0], dim=1).contiguous()
+    ws2 = dev.propagate_workspace(g, g2.dtype, 2 * F, K)
+    out2 = torch.empty_like(g2)
+    two_ms = event_ms(lambda: (dev.propagate_bwd(g, gY, K, out=out_b, ws=ws), dev.propagate_bwd(g, X0, K, out=out_b, ws=ws)), reps=3)
+    one_ms = event_ms(lambda: dev.propagate_bwd(g, g2, K, out=out2, ws=ws2), reps=3)
+    gfae["two_backward_passes_ms"] = round(two_ms, 4)
+    gfae["one_stacked_backward_pass_ms"] = round(one_ms, 4)
+    del g2, ws2, out2
 
     # roofline of the neighbour-sum kernel: algorithmic bytes of one layer over its mean duration
     alg_bytes = 4 * nnz + 4 * (n + 1) + 4 * n + 2 * n * F * esz

@@ -93,3 +93,23 @@ def test_loss_is_reproducible(dev):
     a = dev.gfae_loss(X, Y, want_grad=False)[0].item()
     b = dev.gfae_loss(X, Y, want_grad=False)[0].item()
     assert a == b
+
+
+def test_two_upstream_gradients_in_one_pass(dev, oracle):
+    """The per-task gradients that GradNorm needs with respect to h(0) (Section 4.3.1): the
+    propagation acts on every feature column independently, so two upstream gradients stacked
+    side by side as [n, 2F] go through one backward pass; each half must match its own pass."""
+    c = make_config(3, scale=0.02)
+    K, dt, F = c["K"], c["dtype"], c["F"]
+    u = torch.from_numpy(c["users"]).cuda()
+    i = torch.from_numpy(c["items"]).cuda()
+    g = dev.build_graph(c["n_users"], c["n_items"], u, i)
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    g1, g2 = to_device(c["gY"], dt), to_device(c["X0"], dt)
+    both = torch.cat([g1, g2], dim=1).contiguous()
+    out = dev.propagate_bwd(g, both, K)
+    torch.cuda.synchronize()
+    for half, src in ((out[:, :F], c["gY"]), (out[:, F:], c["X0"])):
+        ref = oracle.propagate_bwd(row_ptr, col, src, K)
+        sc = oracle.propagate_bwd(row_ptr, col, np.abs(oracle.as_f64(src)), K)
+        assert_close(to_f64(half), ref, sc, dt, "stacked backward")
