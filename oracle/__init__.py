@@ -52,6 +52,8 @@ def _load():
         lib.e2eg_oracle_propagate_layer_transposed.argtypes = lib.e2eg_oracle_propagate_layer.argtypes
         lib.e2eg_oracle_propagate_rows.argtypes = [ctypes.c_int64, _i64p, _i64p, _i32p, ctypes.c_int64,
                                                    _f64p, _f64p]
+        lib.e2eg_oracle_mean_neighbours.argtypes = [ctypes.c_int64, _i64p, _i32p, ctypes.c_int64, _f64p, _f64p]
+        lib.e2eg_oracle_mean_neighbours_transposed.argtypes = lib.e2eg_oracle_mean_neighbours.argtypes
         lib.e2eg_oracle_readout_mean.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
         lib.e2eg_oracle_gfae_loss.restype = ctypes.c_double
         lib.e2eg_oracle_gfae_loss.argtypes = [ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
@@ -246,3 +248,43 @@ def transform_bwd(P, W, mask, gH, relu=True):
     _load().e2eg_oracle_transform_bwd(n, Fin, Fout, _p(P, _f64p), _p(W, _f64p), _p(mask, _f64p),
                                       _p(gH, _f64p), 1 if relu else 0, _p(dP, _f64p), _p(dW, _f64p))
     return dP, dW
+
+
+def mean_neighbours(row_ptr, col_idx, X):
+    """GraphSAGE mean aggregator: row i -> mean of X over the row's neighbours (0 if none)."""
+    row_ptr = _c(row_ptr, np.int64)
+    col_idx = _c(col_idx, np.int32)
+    X = as_f64(X)
+    n, F = X.shape
+    M = np.empty_like(X)
+    _load().e2eg_oracle_mean_neighbours(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), F, _p(X, _f64p), _p(M, _f64p))
+    return M
+
+
+def mean_neighbours_transposed(row_ptr, col_idx, gM):
+    """Transpose of the mean aggregator applied to gM (scatter over the same CSR)."""
+    row_ptr = _c(row_ptr, np.int64)
+    col_idx = _c(col_idx, np.int32)
+    gM = as_f64(gM)
+    n, F = gM.shape
+    G = np.empty_like(gM)
+    _load().e2eg_oracle_mean_neighbours_transposed(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), F, _p(gM, _f64p),
+                                                   _p(G, _f64p))
+    return G
+
+
+def sage_layer_fwd(row_ptr, col_idx, H, W, relu=True):
+    """GraphSAGE layer: C = CONCAT(H, mean of neighbours), Z = C W (W is [2F][Fout]), H' = relu(Z).
+    -> (C, Z, H')."""
+    H = as_f64(H)
+    C = np.concatenate([H, mean_neighbours(row_ptr, col_idx, H)], axis=1)
+    Z, Hn = transform_fwd(C, W, relu)
+    return C, Z, Hn
+
+
+def sage_layer_bwd(row_ptr, col_idx, C, W, mask, gHn, relu=True):
+    """Backward of sage_layer_fwd: -> (dL/dH, dL/dW) given dL/dH' and the sign pattern `mask` of Z."""
+    F = C.shape[1] // 2
+    dC, dW = transform_bwd(C, W, mask, gHn, relu)
+    gH = dC[:, :F] + mean_neighbours_transposed(row_ptr, col_idx, np.ascontiguousarray(dC[:, F:]))
+    return gH, dW

@@ -26,6 +26,9 @@
  *   - Layer combination of LightGCN, Y = 1/(L+1) sum_{l=0..L} H(l) (Section 3.1, the final
  *     representation as the mean of all layers), and the GFAE reconstruction loss with the
  *     identity decoder, L_ssl = ||X - Y||_F^2 (Section 4.2), with dL/dY = 2 (Y - X).
+ *   - GraphSAGE layer (Section 3.1): mean of the neighbours' rows, hbar_u = 1/|S(u)| sum_{v in S(u)} h_v
+ *     with S(u) the node's neighbours in the given (sampled) graph, then
+ *     h'_u = sigma(W . CONCAT(h_u, hbar_u)); sigma = ReLU here.
  *   - Dense per-layer update Z = P W, H' = max(Z, 0): the update function psi of
  *     the generic message-passing layer with the W, sigma of the GraphSAGE
  *     layer (Section 3 and Section 3.1), and its backward.
@@ -239,4 +242,40 @@ double e2eg_oracle_gfae_loss(int64_t n, int64_t F, const double* X, const double
         if (gY) gY[k] = 2.0 * (Y[k] - X[k]);
     }
     return loss;
+}
+
+/*
+ * Mean aggregator of GraphSAGE (Section 3.1):  M_i = 1/|N(i)| * sum_{j in row i} X_j, the rows of
+ * the CSR being the neighbour sets (built without self-loops); an empty row gives 0.
+ */
+void e2eg_oracle_mean_neighbours(int64_t n, const int64_t* row_ptr, const int32_t* col_idx, int64_t F,
+                                 const double* X, double* M) {
+    for (int64_t i = 0; i < n; ++i) {
+        double* m = M + i * F;
+        int64_t d = row_ptr[i + 1] - row_ptr[i];
+        for (int64_t f = 0; f < F; ++f) m[f] = 0.0;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            const double* x = X + (int64_t)col_idx[p] * F;
+            for (int64_t f = 0; f < F; ++f) m[f] += x[f];
+        }
+        if (d > 0)
+            for (int64_t f = 0; f < F; ++f) m[f] /= (double)d;
+    }
+}
+
+/*
+ * Transpose of the mean aggregator, scatter form over the same CSR:  G_j += gM_i / |N(i)| for every
+ * stored (i, j).  It is the transpose whatever the structure.
+ */
+void e2eg_oracle_mean_neighbours_transposed(int64_t n, const int64_t* row_ptr, const int32_t* col_idx,
+                                            int64_t F, const double* gM, double* G) {
+    for (int64_t k = 0; k < n * F; ++k) G[k] = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t d = row_ptr[i + 1] - row_ptr[i];
+        const double* g = gM + i * F;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            double* o = G + (int64_t)col_idx[p] * F;
+            for (int64_t f = 0; f < F; ++f) o[f] += g[f] / (double)d;
+        }
+    }
 }

@@ -10,6 +10,7 @@
    also on a deliberately non-symmetric structure;
  * an independent library evaluation (scipy.sparse);
  * the per-node LightGCN update of Section 3.1 written as python loops (no self-loop variant);
+ * GraphSAGE: dense D^-1 A written from the layer's definition, the star's centre, finite differences;
  * layer-mean readout and GFAE loss: a hand-worked single-edge case (tests/golden/), the dense
    mean of powers of A^, numpy's Frobenius norm, finite differences of the whole chain.
 """
@@ -549,3 +550,67 @@ def test_shared_direct_terms_equal_explicit_ones(oracle):
     a = oracle.propagate_bwd(row_ptr, col, gK, K, g_shared=g)
     b = oracle.propagate_bwd(row_ptr, col, gK, K, g_layers=[g] * (K - 1)) + g
     assert relerr(a, b) < 1e-14
+
+
+# ---------------------------------------------------------------- GraphSAGE layer
+def test_mean_aggregator_matches_dense(oracle):
+    nu, ni, u, i = small_graph(6)
+    n = nu + ni
+    _, At = dense_ahat(nu, ni, u, i)
+    A = At - np.eye(n)                                   # neighbour sets, no self-loop
+    d = A.sum(1)
+    Dinv = np.diag(np.where(d > 0, 1.0 / np.where(d > 0, d, 1.0), 0.0))
+    row_ptr, col = oracle.build_csr(nu, ni, u, i, add_self_loops=False)
+    X = np.random.default_rng(6).standard_normal((n, 5))
+    assert relerr(oracle.mean_neighbours(row_ptr, col, X), Dinv @ A @ X) < 1e-13
+    G = np.random.default_rng(7).standard_normal((n, 5))
+    assert relerr(oracle.mean_neighbours_transposed(row_ptr, col, G), (Dinv @ A).T @ G) < 1e-13
+    # one-slip variants are out of reach: sum instead of mean, symmetric normalisation, self included
+    assert relerr(oracle.mean_neighbours(row_ptr, col, X), A @ X) > 1e-3
+    s = np.where(d > 0, np.where(d > 0, d, 1.0) ** -0.5, 0.0)
+    assert relerr(oracle.mean_neighbours(row_ptr, col, X), np.diag(s) @ A @ np.diag(s) @ X) > 1e-3
+    assert relerr(oracle.mean_neighbours(row_ptr, col, X), np.diag(1.0 / (d + 1)) @ At @ X) > 1e-3
+
+
+def test_mean_aggregator_star_and_isolated(oracle):
+    # one item joined to 4 users, plus an item nobody touched
+    row_ptr, col = oracle.build_csr(4, 2, np.arange(4, dtype=np.int32), np.zeros(4, np.int32), add_self_loops=False)
+    X = np.arange(12, dtype=np.float64).reshape(6, 2)
+    M = oracle.mean_neighbours(row_ptr, col, X)
+    assert np.array_equal(M[4], X[:4].mean(0))           # the centre: average of its four users
+    assert np.array_equal(M[:4], np.tile(X[4], (4, 1)))  # each user: its only neighbour
+    assert not M[5].any()                                # empty neighbourhood: zero
+
+
+def test_sage_layer_matches_numpy_and_finite_differences(oracle):
+    nu, ni, u, i = small_graph(9, nu=7, ni=5, ne=18)
+    n, F, Fo = nu + ni, 3, 4
+    row_ptr, col = oracle.build_csr(nu, ni, u, i, add_self_loops=False)
+    rng = np.random.default_rng(2)
+    H = rng.standard_normal((n, F))
+    W = rng.standard_normal((2 * F, Fo))
+    _, At = dense_ahat(nu, ni, u, i)
+    A = At - np.eye(n)
+    d = A.sum(1)
+    Mdense = np.diag(np.where(d > 0, 1.0 / np.where(d > 0, d, 1.0), 0.0)) @ A
+    C, Z, Hn = oracle.sage_layer_fwd(row_ptr, col, H, W)
+    assert relerr(Z, np.concatenate([H, Mdense @ H], axis=1) @ W) < 1e-13
+    assert np.array_equal(Hn, np.maximum(Z, 0))
+    R = rng.standard_normal((n, Fo))                     # L = <relu(Z), R>
+    gH, dW = oracle.sage_layer_bwd(row_ptr, col, C, W, Z, R)
+
+    def loss(Hv, Wv):
+        return float((oracle.sage_layer_fwd(row_ptr, col, Hv, Wv)[2] * R).sum())
+
+    h = 1e-6
+    for _ in range(10):
+        r, c = rng.integers(0, n), rng.integers(0, F)
+        Hp, Hm = H.copy(), H.copy()
+        Hp[r, c] += h
+        Hm[r, c] -= h
+        assert abs((loss(Hp, W) - loss(Hm, W)) / (2 * h) - gH[r, c]) < 1e-6
+        r, c = rng.integers(0, 2 * F), rng.integers(0, Fo)
+        Wp, Wm = W.copy(), W.copy()
+        Wp[r, c] += h
+        Wm[r, c] -= h
+        assert abs((loss(H, Wp) - loss(H, Wm)) / (2 * h) - dW[r, c]) < 1e-6
