@@ -52,6 +52,11 @@ extern "C" {
 
 #define E2EG_ADD_SELF_LOOPS 1 /* build_csr flag bit 0: build A~ = A + I (else A itself) */
 
+#define E2EG_AGG_SYM 0    /* D^-1/2 M D^-1/2 of the stored structure M (A^ when built with self-loops)  */
+#define E2EG_AGG_MEAN 1   /* D^-1 M: the mean over each row's neighbours (0 for an empty row)          */
+#define E2EG_AGG_MEAN_T 2 /* M D^-1: the transpose of E2EG_AGG_MEAN on a symmetric structure           */
+#define E2EG_AGG_SUM 3    /* M itself: the plain neighbour sum                                          */
+
 #define E2EG_TRANSFORM_FWD 0
 #define E2EG_TRANSFORM_BWD 1
 
@@ -134,6 +139,27 @@ int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
                            size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * e2eg_aggregate: one neighbourhood aggregation  Y = S_out M S_in X (+ addend)  over the stored
+ * structure M (d_row_ptr / d_col_idx and the schedule e2eg_normalize made for them), with diagonal
+ * scales chosen by `mode` from the row lengths d_i:
+ *   E2EG_AGG_MEAN   the mean aggregator of the GraphSAGE layer (Section 3.1),
+ *                   hbar_u = 1/|S(u)| sum_{v in S(u)} h_v, with S(u) = row u of a structure built
+ *                   WITHOUT self-loops (the sampled neighbours); an empty row gives 0;
+ *   E2EG_AGG_MEAN_T its transpose, for the backward (the structure must be symmetric);
+ *   E2EG_AGG_SYM    d_i^-1/2 d_j^-1/2 weights: one layer of e2eg_propagate_fwd;
+ *   E2EG_AGG_SUM    no scaling.
+ * d_X [n][F] (ldx) in, d_Y [n][F] (ldy) out, must not overlap; d_addend (may be NULL) [n][F]
+ * (ld_add) is added to the result before it is stored (it may be d_Y's neighbour in a wider
+ * array but must not overlap d_Y).  ldy > F lets the result land in one half of a CONCAT buffer.
+ * fp32 accumulation, one rounding to the storage type.
+ */
+size_t e2eg_aggregate_workspace_bytes(int32_t n, int64_t nnz, int32_t dtype, int32_t F);
+int32_t e2eg_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                       const int32_t* d_col_idx, const void* d_sched, int32_t dtype, int32_t F,
+                       const void* d_X, int64_t ldx, const void* d_addend, int64_t ld_add, void* d_Y,
+                       int64_t ldy, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * e2eg_layer_transform: the dense per-layer update (update function psi of the generic
  * message-passing layer with the W, sigma of the GraphSAGE layer; Section 3, Section 3.1).
  *
@@ -145,6 +171,8 @@ int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
  *     d_gW [Fin][Fout] fp32 out (overwritten, not accumulated).  d_gP or d_gW may be NULL
  *     to skip that product.
  * dtype E2EG_BF16 only (bf16 MFMA, fp32 accumulate); Fin and Fout multiples of 32, <= 256.
+ * With d_P = CONCAT(h, hbar) ([n][2F], hbar written there by e2eg_aggregate) and d_W [2F][Fout]
+ * this is the update of the GraphSAGE layer, h' = sigma(W . CONCAT(h, hbar)) (Section 3.1).
  */
 size_t e2eg_layer_transform_workspace_bytes(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
                                             int32_t dtype);

@@ -23,6 +23,7 @@ E2EG_ERR_BAD_INDEX = -8
 E2EG_F32 = 0
 E2EG_BF16 = 1
 E2EG_ADD_SELF_LOOPS = 1
+E2EG_AGG_SYM, E2EG_AGG_MEAN, E2EG_AGG_MEAN_T, E2EG_AGG_SUM = 0, 1, 2, 3
 E2EG_TRANSFORM_FWD = 0
 E2EG_TRANSFORM_BWD = 1
 
@@ -43,6 +44,8 @@ SIGNATURES = {
     "e2eg_propagate_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_layer_transform_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "e2eg_aggregate_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
+    "e2eg_aggregate": (_i32, [_i32, _i32, _i64, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_readout_mean": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
     "e2eg_gfae_loss_workspace_bytes": (_sz, [_i32, _i32]),
     "e2eg_gfae_loss": (_i32, [_i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _sz, _vp]),
@@ -196,3 +199,14 @@ def e2eg_gfae_loss(n, dtype, F, d_X, ldx, d_Y, ldy, d_loss, d_gY, ldg, grad_scal
     _check(load_library().e2eg_gfae_loss(n, dtype, F, _ptr(d_X), ldx, _ptr(d_Y), ldy, _ptr(d_loss), _ptr(d_gY), ldg,
                                          grad_scale, _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
                                          stream or None))
+
+
+def e2eg_aggregate_workspace_bytes(n, nnz, dtype, F) -> int:
+    return int(load_library().e2eg_aggregate_workspace_bytes(n, nnz, dtype, F))
+
+
+def e2eg_aggregate(mode, n, nnz, d_row_ptr, d_col_idx, d_sched, dtype, F, d_X, ldx, d_addend, ld_add, d_Y, ldy, ws,
+                   ws_bytes=None, stream=0):
+    _check(load_library().e2eg_aggregate(mode, n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_sched), dtype, F,
+                                         _ptr(d_X), ldx, _ptr(d_addend), ld_add, _ptr(d_Y), ldy, _ptr(ws),
+                                         _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))

@@ -629,6 +629,71 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     return E2EG_OK;
 }
 
+// Per-node input and output scales of e2eg_aggregate, from the row lengths of the caller's CSR.
+__global__ void aggregate_scales(const int32_t* __restrict__ row_ptr, int64_t n, int32_t mode,
+                                 float* __restrict__ scale_in, float* __restrict__ scale_out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t d = row_ptr[i + 1] - row_ptr[i];
+    const float inv = d > 0 ? (float)(1.0 / (double)d) : 0.0f;
+    const float rs = d > 0 ? (float)(1.0 / sqrt((double)d)) : 0.0f;
+    float in = 1.0f, out = 1.0f;
+    if (mode == E2EG_AGG_SYM) in = out = rs;
+    else if (mode == E2EG_AGG_MEAN) out = inv;
+    else if (mode == E2EG_AGG_MEAN_T) in = inv;
+    scale_in[i] = in;
+    scale_out[i] = out;
+}
+
+struct AggWs {
+    void* z;
+    float* partial;
+    float* scale_in;
+    float* scale_out;
+    size_t bytes;
+};
+
+AggWs carve_agg(void* base, int64_t n, int64_t nnz, int32_t dtype, int32_t F) {
+    Carver c(base);
+    AggWs w;
+    const size_t esz = dtype == E2EG_F32 ? 4 : 2;
+    w.z = c.take<char>((size_t)(n + 1) * (size_t)F * esz);
+    w.partial = c.take<float>((size_t)sched_max_slot(n, nnz) * (size_t)F);
+    w.scale_in = c.take<float>(n > 0 ? n : 1);
+    w.scale_out = c.take<float>(n > 0 ? n : 1);
+    w.bytes = c.size();
+    return w;
+}
+
+template <typename T>
+int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_ptr, const void* sched, int32_t F,
+                      const void* x, int64_t ldx, const void* addend, int64_t ld_add, void* y, int64_t ldy,
+                      const AggWs& w, hipStream_t stream) {
+    using E = typename T::elem;
+    SchedView view;
+    sched_carve(const_cast<void*>(sched), n, nnz, &view);
+    aggregate_scales<<<dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream>>>(row_ptr, n, mode, w.scale_in,
+                                                                                w.scale_out);
+    E2EG_LAUNCH_CHECK("aggregate_scales");
+    const int chunks = F / T::kVec;
+    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kPrescaleThreads)),
+                       dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(x), ldx, w.scale_in, view.orig,
+                                                            static_cast<E*>(w.z), nullptr, n, F);
+    E2EG_LAUNCH_CHECK("prescale_rows");
+    LayerArgs<T> a;
+    a.dinv_sqrt = w.scale_out;
+    a.sched = view;
+    a.zin = static_cast<const E*>(w.z);
+    a.out_h = static_cast<E*>(y);
+    a.ld_h = ldy;
+    a.out_z = nullptr;
+    a.addend = static_cast<const E*>(addend);
+    a.ld_add = ld_add;
+    a.partial = w.partial;
+    a.F = F;
+    return launch_layer<T>(a, n, nnz, stream);
+}
+
 constexpr int kMaxLayers = 64;
 
 }  // namespace
@@ -737,4 +802,33 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
     }
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
                             lds, add, ldg, w, stream);
+}
+
+extern "C" size_t e2eg_aggregate_workspace_bytes(int32_t n, int64_t nnz, int32_t dtype, int32_t F) {
+    if (n < 0 || nnz < 0 || F <= 0 || (dtype != E2EG_F32 && dtype != E2EG_BF16)) return 0;
+    return carve_agg(nullptr, n, nnz, dtype, F).bytes;
+}
+
+extern "C" int32_t e2eg_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                  const int32_t* d_col_idx, const void* d_sched, int32_t dtype, int32_t F,
+                                  const void* d_X, int64_t ldx, const void* d_addend, int64_t ld_add, void* d_Y,
+                                  int64_t ldy, void* ws, size_t ws_bytes, void* stream_) {
+    const char* who = "aggregate";
+    if (mode != E2EG_AGG_SYM && mode != E2EG_AGG_MEAN && mode != E2EG_AGG_MEAN_T && mode != E2EG_AGG_SUM)
+        return fail(E2EG_ERR_INVALID_ARG, "%s: mode %d", who, mode);
+    const float one = 1.0f;  // stands for the scale array in the shared checks; never dereferenced
+    int32_t st = check_common(who, n, nnz, d_row_ptr, d_col_idx, &one, d_sched, dtype, F, 1);
+    if (st != E2EG_OK) return st;
+    if ((st = check_matrix(who, "d_X", d_X, ldx, F, dtype)) != E2EG_OK) return st;
+    if ((st = check_matrix(who, "d_Y", d_Y, ldy, F, dtype)) != E2EG_OK) return st;
+    if (d_addend && (st = check_matrix(who, "d_addend", d_addend, ld_add, F, dtype)) != E2EG_OK) return st;
+    const size_t need = e2eg_aggregate_workspace_bytes(n, nnz, dtype, F);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    if (n == 0) return E2EG_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const AggWs w = carve_agg(ws, n, nnz, dtype, F);
+    if (dtype == E2EG_F32)
+        return run_aggregate<F32>(mode, n, nnz, d_row_ptr, d_sched, F, d_X, ldx, d_addend, ld_add, d_Y, ldy, w, stream);
+    return run_aggregate<BF16>(mode, n, nnz, d_row_ptr, d_sched, F, d_X, ldx, d_addend, ld_add, d_Y, ldy, w, stream);
 }

@@ -173,3 +173,20 @@ def gfae_loss(X: torch.Tensor, Y: torch.Tensor, grad_scale: float = 1.0, want_gr
     B.e2eg_gfae_loss(n, _dtype_code(X), F, X, X.stride(0), Y, Y.stride(0), loss, gY, F, float(grad_scale), ws, None,
                      _stream())
     return loss, gY
+
+
+def aggregate(g: Graph, X: torch.Tensor, mode: int, addend: torch.Tensor | None = None,
+              out: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = S_out M S_in X (+ addend) over the graph's stored structure; X, addend and out may be
+    column slices of wider row-major arrays (stride(1) == 1)."""
+    _require_gpu()
+    n, F = X.shape
+    assert n == g.n and X.stride(1) == 1
+    if out is None:
+        out = torch.empty((n, F), dtype=X.dtype, device=X.device)
+    assert out.shape == (n, F) and out.stride(1) == 1 and out.dtype == X.dtype
+    code = _dtype_code(X)
+    ws = _bytes(B.e2eg_aggregate_workspace_bytes(g.n, g.nnz, code, F), X.device)
+    B.e2eg_aggregate(mode, g.n, g.nnz, g.row_ptr, g.col_idx, g.sched, code, F, X, X.stride(0),
+                     addend, addend.stride(0) if addend is not None else 0, out, out.stride(0), ws, None, _stream())
+    return out

@@ -153,6 +153,28 @@ def test_layer_transform_argument_errors(B):
         == B.E2EG_ERR_WORKSPACE
 
 
+def test_aggregate_argument_errors(B):
+    f = B.e2eg_aggregate
+    ok = dict(mode=B.E2EG_AGG_MEAN, n=10, nnz=30, rp=FAKE, col=FAKE, sched=FAKE, dtype=B.E2EG_F32, F=8, X=FAKE, ldx=8,
+              add=None, lda=0, Y=FAKE, ldy=8, ws=FAKE, wsb=1 << 30)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return status_of(B, f, a["mode"], a["n"], a["nnz"], a["rp"], a["col"], a["sched"], a["dtype"], a["F"], a["X"],
+                         a["ldx"], a["add"], a["lda"], a["Y"], a["ldy"], a["ws"], a["wsb"])
+
+    assert call(mode=9) == B.E2EG_ERR_INVALID_ARG
+    assert call(dtype=5) == B.E2EG_ERR_BAD_DTYPE
+    assert call(F=6) == B.E2EG_ERR_INVALID_ARG
+    assert call(sched=None) == B.E2EG_ERR_NULL_PTR
+    assert call(X=None) == B.E2EG_ERR_NULL_PTR
+    assert call(ldy=4) == B.E2EG_ERR_INVALID_ARG
+    assert call(add=FAKE, lda=4) == B.E2EG_ERR_INVALID_ARG
+    assert call(wsb=16) == B.E2EG_ERR_WORKSPACE
+    assert call(nnz=1 << 31) == B.E2EG_ERR_OVERFLOW
+    assert B.e2eg_aggregate_workspace_bytes(10, 30, B.E2EG_F32, 8) > 0
+
+
 def test_readout_and_gfae_argument_errors(B):
     r = B.e2eg_readout_mean
     assert status_of(B, r, 10, B.E2EG_F32, 6, 2, FAKE, 6, FAKE, 6, 60, FAKE, 6) == B.E2EG_ERR_INVALID_ARG   # F % 4
