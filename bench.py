@@ -171,6 +171,26 @@ def main():
     gfae["one_stacked_backward_pass_ms"] = round(one_ms, 4)
     del g2, ws2, out2
 
+    # the dense per-layer update on the matrix cores at the mini-batch shape (about 200 k sampled
+    # nodes, 128 x 128 weights): forward, and backward (dP and dW); flops and bytes are algorithmic
+    nt, Ft = 200_000, 128
+    Pt = torch.randn(nt, Ft, device="cuda").to(torch.bfloat16)
+    Wt = (torch.randn(Ft, Ft, device="cuda") / Ft ** 0.5).to(torch.bfloat16)
+    gt = torch.randn(nt, Ft, device="cuda").to(torch.bfloat16)
+    Ht = dev.layer_transform_fwd(Pt, Wt, relu=True)
+    tf_ms = event_ms(lambda: dev.layer_transform_fwd(Pt, Wt, relu=True), reps=10)
+    tb_ms = event_ms(lambda: dev.layer_transform_bwd(Pt, Wt, Ht, gt, relu=True), reps=10)
+    flop_f = 2.0 * nt * Ft * Ft
+    transform = {
+        "rows": nt, "Fin": Ft, "Fout": Ft,
+        "fwd_ms": round(tf_ms, 4), "fwd_TFLOPs": round(flop_f / tf_ms / 1e9, 1),
+        "fwd_GBs": round((2 * nt * Ft * 2 + Ft * Ft * 2) / tf_ms / 1e6, 1),
+        "bwd_ms": round(tb_ms, 4), "bwd_TFLOPs": round(2 * flop_f / tb_ms / 1e9, 1),
+        "bwd_GBs": round((4 * nt * Ft * 2 + Ft * Ft * 6) / tb_ms / 1e6, 1),
+        "mfma_bf16_peak_TFLOPs": 2500.0, "hbm_peak_GBs": HBM_PEAK_GBS,
+    }
+    del Pt, gt, Ht
+
     # roofline of the neighbour-sum kernel: algorithmic bytes of one layer over its mean duration
     alg_bytes = 4 * nnz + 4 * (n + 1) + 4 * n + 2 * n * F * esz
     gather_bytes = alg_bytes - n * F * esz + nnz * F * esz + 4 * nnz
@@ -218,7 +238,7 @@ def main():
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
         "build_csr_ms": round(build_ms - normalize_ms, 3), "normalize_ms": round(normalize_ms, 3),
         "alg_GBs": round(alg_bytes * 2 * K / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae,
+        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae, "layer_transform": transform,
     }
     print(json.dumps(line), flush=True)
 

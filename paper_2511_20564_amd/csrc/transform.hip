@@ -53,14 +53,15 @@ __device__ __forceinline__ uint4 mask_vec(uint4 g, uint4 h) {
 
 // out[r][c] = act( sum_k A[r][k] * B(c, k) ),  A = rows of `a_rows` (masked by `mask_rows` > 0
 // when MASKED), B(c, k) = TRANS_W ? w[k][c] : w[c][k].
-// grid.x: blocks of 128 rows; grid.y: groups of `ngroup` output columns.
+// grid.x: blocks of `tiles` x 128 rows (the weight tile is staged once per workgroup and serves
+// all its row tiles); grid.y: groups of `ngroup` output columns.
 template <bool MASKED, bool TRANS_W, bool RELU>
 __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restrict__ a_rows,
                                                        const uint16_t* __restrict__ mask_rows,
                                                        const uint16_t* __restrict__ w,
                                                        uint16_t* __restrict__ out, int32_t n,
                                                        int32_t kdim, int32_t ndim, int32_t w_ld,
-                                                       int32_t ngroup) {
+                                                       int32_t ngroup, int32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][kdim + kPad]
     const int ldb = kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
@@ -92,10 +93,13 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
     const int khalf = lane >> 5;
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave * 32 + l32;
-    const bool live = row < n;
     const int ksteps = kdim / 16;
     const int nblocks = ng / 32;
+#pragma unroll 1
+    for (int tile = 0; tile < tiles; ++tile) {
+    const int64_t row = ((int64_t)blockIdx.x * tiles + tile) * kRowsPerBlock + wave * 32 + l32;
+    if ((int64_t)row - l32 >= n) return;   // the whole wavefront is past the end
+    const bool live = row < n;
 
     uint4 areg[kMaxF / 16];
 #pragma unroll
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
             }
         }
     }
-    if (!live) return;
+    if (!live) continue;
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
         if (nb < nblocks) {
@@ -143,6 +147,7 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
                 *reinterpret_cast<uint2*>(out + row * ndim + col) = q;
             }
         }
+    }
     }
 }
 
@@ -230,17 +235,34 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     }
 }
 
-__global__ void weight_grad_reduce(const float* __restrict__ partial, int32_t nblocks, int32_t count,
-                                   float* __restrict__ gw) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= count) return;
+// gw[e] = sum over blocks of partial[b][e], in double and in a fixed order: thread (q, j) of a
+// workgroup adds blocks q, q + 4, q + 8, ... for element e0 + j; the four sums of an element are
+// then added in q order.
+constexpr int kReduceElems = 64;   // elements per workgroup
+constexpr int kReduceSlices = kThreads / kReduceElems;
+
+__global__ __launch_bounds__(kThreads) void weight_grad_reduce(const float* __restrict__ partial, int32_t nblocks,
+                                                               int32_t count, float* __restrict__ gw) {
+    __shared__ double red[kReduceSlices][kReduceElems];
+    const int j = threadIdx.x % kReduceElems, q = threadIdx.x / kReduceElems;
+    const int e = blockIdx.x * kReduceElems + j;
     double s = 0.0;
-    for (int32_t b = 0; b < nblocks; ++b) s += (double)partial[(int64_t)b * count + e];
-    gw[e] = (float)s;
+    if (e < count)
+        for (int32_t b = q; b < nblocks; b += kReduceSlices) s += (double)partial[(int64_t)b * count + e];
+    red[q][j] = s;
+    __syncthreads();
+    if (q == 0 && e < count) {
+        double t = red[0][j];
+#pragma unroll
+        for (int k = 1; k < kReduceSlices; ++k) t += red[k][j];
+        gw[e] = (float)t;
+    }
 }
 
+// Node rows per workgroup of weight_grad_partial: about one workgroup per compute unit, so that
+// few partial matrices are written and read back.
 int32_t rows_per_block_for(int32_t n) {
-    int64_t r = ceil_div(n > 0 ? n : 1, 512);
+    int64_t r = ceil_div(n > 0 ? n : 1, 256);
     r = (r + kTileRows - 1) / kTileRows * kTileRows;
     return (int32_t)(r < 128 ? 128 : r);
 }
@@ -249,10 +271,12 @@ template <bool MASKED, bool TRANS_W, bool RELU>
 void launch_dense(const void* a, const void* mask, const void* w, void* out, int32_t n, int32_t kdim,
                   int32_t ndim, int32_t w_ld, hipStream_t stream) {
     const int32_t ngroup = kdim > 128 ? 64 : 128;
-    const dim3 grid((unsigned)ceil_div(n, kRowsPerBlock), (unsigned)ceil_div(ndim, ngroup));
+    int64_t tiles = ceil_div(n, (int64_t)kRowsPerBlock * 512);   // keep at least ~512 workgroups
+    tiles = tiles < 1 ? 1 : (tiles > 8 ? 8 : tiles);
+    const dim3 grid((unsigned)ceil_div(n, kRowsPerBlock * tiles), (unsigned)ceil_div(ndim, ngroup));
     dense_rows<MASKED, TRANS_W, RELU><<<grid, dim3(kThreads), 0, stream>>>(
         static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
-        static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup);
+        static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles);
 }
 
 }  // namespace
@@ -317,7 +341,7 @@ extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, in
             E2EG_LAUNCH_CHECK("weight_grad_partial");
         }
         const int32_t count = Fin * Fout;
-        weight_grad_reduce<<<dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream>>>(partial, blocks, count, d_gW);
+        weight_grad_reduce<<<dim3((unsigned)ceil_div(count, kReduceElems)), dim3(kThreads), 0, stream>>>(partial, blocks, count, d_gW);
         E2EG_LAUNCH_CHECK("weight_grad_reduce");
     }
     return E2EG_OK;
