@@ -162,6 +162,30 @@ def test_propagate_many_tiny_segments(dev, oracle):
     run_case(dev, oracle, c)
 
 
+@pytest.mark.parametrize("nu,item_degs", [
+    (600, [128, 129, 127, 1, 0, 512, 513, 511, 600]),               # the cut-off lengths of the row classes
+    (8190, [2, 3, 8190, 5000]),                                     # n just below / at the renumbered block
+    (8191, [1, 8191]),
+    (8200, [8200, 4096, 513, 513, 513]),                            # two windows, rows crossing the boundary
+    (16383, [16383, 9000, 1]),
+    (16390, [16390, 700] + [130] * 40),
+    (40000, [40000, 20000, 3000, 1025] + [64] * 50),                # five windows, rows of every class
+])
+def test_propagate_boundary_sizes(dev, oracle, nu, item_degs):
+    """Graphs built so that row lengths and node counts sit on the limits the schedule branches
+    on: 128/129 and 512/513 entries, node counts around the size of the renumbered block and of
+    the column windows."""
+    rng = np.random.default_rng(nu)
+    ni = len(item_degs)
+    users = np.concatenate([rng.choice(nu, size=d, replace=False) for d in item_degs] + [np.zeros(0, np.int64)])
+    items = np.repeat(np.arange(ni), item_degs)
+    n, F = nu + ni, 16
+    c = dict(n_users=nu, n_items=ni, users=users.astype(np.int32), items=items.astype(np.int32), dtype="f32", K=2,
+             X0=make_features(n, F, 0.1, 1, "f32"), gY=make_features(n, F, 1.0, 2, "f32"))
+    run_case(dev, oracle, c)
+    run_case(dev, oracle, c, self_loops=False)
+
+
 def test_propagate_without_self_loops(dev, oracle):
     nu, ni, ne = 50, 400, 900         # leaves many items without neighbours
     users, items = uniform_bipartite(nu, ni, ne, seed=5)
