@@ -54,6 +54,10 @@ def _load():
                                                    _f64p, _f64p]
         lib.e2eg_oracle_mean_neighbours.argtypes = [ctypes.c_int64, _i64p, _i32p, ctypes.c_int64, _f64p, _f64p]
         lib.e2eg_oracle_mean_neighbours_transposed.argtypes = lib.e2eg_oracle_mean_neighbours.argtypes
+        lib.e2eg_oracle_block_norms.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p]
+        lib.e2eg_oracle_gradnorm_step.restype = ctypes.c_double
+        lib.e2eg_oracle_gradnorm_step.argtypes = [ctypes.c_int64, _f64p, _f64p, _f64p, ctypes.c_double, ctypes.c_double,
+                                                  _f64p]
         lib.e2eg_oracle_readout_mean.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
         lib.e2eg_oracle_gfae_loss.restype = ctypes.c_double
         lib.e2eg_oracle_gfae_loss.argtypes = [ctypes.c_int64, ctypes.c_int64, _f64p, _f64p, _f64p]
@@ -288,3 +292,22 @@ def sage_layer_bwd(row_ptr, col_idx, C, W, mask, gHn, relu=True):
     dC, dW = transform_bwd(C, W, mask, gHn, relu)
     gH = dC[:, :F] + mean_neighbours_transposed(row_ptr, col_idx, np.ascontiguousarray(dC[:, F:]))
     return gH, dW
+
+
+def block_norms(G, T):
+    """2-norms of the T column blocks of G ([n, T*F])."""
+    G = as_f64(G)
+    n, TF = G.shape
+    assert TF % T == 0
+    out = np.empty(T, dtype=np.float64)
+    _load().e2eg_oracle_block_norms(n, TF // T, T, _p(_c(G, np.float64), _f64p), _p(out, _f64p))
+    return out
+
+
+def gradnorm_step(loss, loss0, gnorm, w, gamma=1.0, lr=0.025):
+    """One GradNorm weight update.  -> (meta-loss before the step, new weights)."""
+    loss, loss0, gnorm = (_c(np.asarray(a, dtype=np.float64), np.float64) for a in (loss, loss0, gnorm))
+    w = _c(np.array(w, dtype=np.float64), np.float64)
+    meta = _load().e2eg_oracle_gradnorm_step(w.size, _p(loss, _f64p), _p(loss0, _f64p), _p(gnorm, _f64p),
+                                             float(gamma), float(lr), _p(w, _f64p))
+    return float(meta), w

@@ -29,6 +29,9 @@
  *   - GraphSAGE layer (Section 3.1): mean of the neighbours' rows, hbar_u = 1/|S(u)| sum_{v in S(u)} h_v
  *     with S(u) the node's neighbours in the given (sampled) graph, then
  *     h'_u = sigma(W . CONCAT(h_u, hbar_u)); sigma = ReLU here.
+ *   - GradNorm task weighting (Section 4.3.1): G_i = || grad_{h(0)} (w_i L_i) ||_2, relative rates
+ *     r_i = (L_i / L_i(0)) / mean_j (L_j / L_j(0)), meta-loss sum_i | G_i - Gbar r_i^gamma |, one
+ *     gradient step on the weights and renormalisation to sum_i w_i = T.
  *   - Dense per-layer update Z = P W, H' = max(Z, 0): the update function psi of
  *     the generic message-passing layer with the W, sigma of the GraphSAGE
  *     layer (Section 3 and Section 3.1), and its backward.
@@ -278,4 +281,47 @@ void e2eg_oracle_mean_neighbours_transposed(int64_t n, const int64_t* row_ptr, c
             for (int64_t f = 0; f < F; ++f) o[f] += g[f] / (double)d;
         }
     }
+}
+
+/* 2-norms of the T column blocks of G ([n][T*F]): norms[t] = sqrt(sum_rows sum_{c in block t} G^2). */
+void e2eg_oracle_block_norms(int64_t n, int64_t F, int64_t T, const double* G, double* norms) {
+    for (int64_t t = 0; t < T; ++t) {
+        double s = 0.0;
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t f = 0; f < F; ++f) {
+                double v = G[i * T * F + t * F + f];
+                s += v * v;
+            }
+        norms[t] = sqrt(s);
+    }
+}
+
+/*
+ * One GradNorm step (Section 4.3.1).  gnorm[i] = || grad_{h(0)} L_i ||_2 (without the weight), so
+ * G_i = w_i gnorm[i].  With the targets Gbar r_i^gamma held constant, d/dw_i of
+ * sum_i | G_i - Gbar r_i^gamma | is sign(G_i - Gbar r_i^gamma) gnorm[i]; the weights take one step
+ * of size lr against it, are kept positive (floor 1e-8) and rescaled to sum to T.
+ * Returns the meta-loss at the weights given (before the step).
+ */
+double e2eg_oracle_gradnorm_step(int64_t T, const double* loss, const double* loss0, const double* gnorm,
+                                 double gamma, double lr, double* w) {
+    double Gbar = 0.0, rbar = 0.0, meta = 0.0, sum = 0.0;
+    for (int64_t i = 0; i < T; ++i) {
+        Gbar += w[i] * gnorm[i] / (double)T;
+        rbar += loss[i] / loss0[i] / (double)T;
+    }
+    for (int64_t i = 0; i < T; ++i) {
+        double G = w[i] * gnorm[i];
+        double target = Gbar * pow(loss[i] / loss0[i] / rbar, gamma);
+        double diff = G - target;
+        meta += fabs(diff);
+        double sgn = diff > 0.0 ? 1.0 : (diff < 0.0 ? -1.0 : 0.0);
+        w[i] -= lr * sgn * gnorm[i];
+    }
+    for (int64_t i = 0; i < T; ++i) {
+        if (w[i] < 1e-8) w[i] = 1e-8;
+        sum += w[i];
+    }
+    for (int64_t i = 0; i < T; ++i) w[i] *= (double)T / sum;
+    return meta;
 }

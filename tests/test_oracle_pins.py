@@ -614,3 +614,45 @@ def test_sage_layer_matches_numpy_and_finite_differences(oracle):
         Wp[r, c] += h
         Wm[r, c] -= h
         assert abs((loss(H, Wp) - loss(H, Wm)) / (2 * h) - dW[r, c]) < 1e-6
+
+
+# ---------------------------------------------------------------- GradNorm
+def test_gradnorm_step_golden(oracle):
+    g = _golden("gradnorm_two_tasks.txt")
+    meta, w = oracle.gradnorm_step([2.0, 3.0], [4.0, 4.0], [3.0, 1.0], [1.0, 1.0], gamma=1.0, lr=0.1)
+    assert abs(meta - g["meta"]) < 1e-14
+    assert np.allclose(w, [g["w1"], g["w2"]], rtol=1e-15)
+
+
+def test_gradnorm_invariants(oracle):
+    rng = np.random.default_rng(0)
+    for T in (2, 3, 5):
+        loss, loss0, gn = rng.uniform(0.5, 2, T), rng.uniform(0.5, 2, T), rng.uniform(0.1, 3, T)
+        w0 = rng.uniform(0.5, 1.5, T)
+        w0 *= T / w0.sum()
+        meta, w = oracle.gradnorm_step(loss, loss0, gn, w0, gamma=1.5, lr=0.01)
+        assert abs(w.sum() - T) < 1e-12 and (w > 0).all()
+        # the meta-loss the function reports is the formula of Section 4.3.1 written with numpy
+        G = w0 * gn
+        r = (loss / loss0) / (loss / loss0).mean()
+        assert abs(meta - np.abs(G - G.mean() * r ** 1.5).sum()) < 1e-12
+        # the step goes against the derivative of the meta-loss with the targets held constant
+        target = G.mean() * r ** 1.5
+        h = 1e-7
+        for i in range(T):
+            wp, wm = w0.copy(), w0.copy()
+            wp[i] += h
+            wm[i] -= h
+            fd = (np.abs(wp * gn - target).sum() - np.abs(wm * gn - target).sum()) / (2 * h)
+            assert abs(fd - np.sign(G[i] - target[i]) * gn[i]) < 1e-6
+        raw = w0 - 0.01 * np.sign(G - target) * gn
+        assert np.allclose(w, raw * T / raw.sum(), rtol=1e-12)
+    # balanced gradients and equal progress: nothing to correct, the weights stay
+    meta, w = oracle.gradnorm_step([1.0, 1.0], [2.0, 2.0], [2.0, 2.0], [1.0, 1.0])
+    assert meta == 0.0 and np.array_equal(w, [1.0, 1.0])
+
+
+def test_block_norms_match_numpy(oracle):
+    G = np.random.default_rng(5).standard_normal((37, 12))
+    got = oracle.block_norms(G, 3)
+    assert np.allclose(got, [np.linalg.norm(G[:, 4 * t:4 * t + 4]) for t in range(3)], rtol=1e-14)
