@@ -211,6 +211,28 @@ int32_t e2eg_gfae_loss(int32_t n, int32_t dtype, int32_t F, const void* d_X, int
                        size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * GradNorm task weighting (Section 4.3.1).  The gradient norms are taken with respect to the
+ * shared input features h(0): G_i = || grad_{h(0)} (w_i L_i) ||_2 = w_i || grad_{h(0)} L_i ||_2.
+ *
+ * e2eg_block_norms: the per-task gradients grad_{h(0)} L_i, i = 0..T-1, stand side by side as the
+ * column blocks of d_G [n][T*F] (ld) - which is how one call of e2eg_propagate_bwd on T stacked
+ * upstream gradients leaves them.  d_norms (DEVICE double[T]) receives the 2-norm of each block,
+ * summed in double in a fixed order.  1 <= T <= 8.
+ *
+ * e2eg_gradnorm_step: host arithmetic on host arrays of length T.  With r_i = (L_i / L_i(0)) /
+ * mean_j (L_j / L_j(0)) and Gbar = mean_i w_i gnorm_i, the meta-loss is sum_i |w_i gnorm_i - Gbar
+ * r_i^gamma|; its derivative in w_i with the targets Gbar r_i^gamma held constant is
+ * sign(w_i gnorm_i - Gbar r_i^gamma) gnorm_i.  h_w takes one step of size lr against it, is kept
+ * positive (floor 1e-8) and rescaled so that sum_i w_i = T.  *h_meta_loss (may be NULL) receives the
+ * meta-loss at the weights passed in.  Initial losses and weights must be positive.
+ */
+size_t e2eg_block_norms_workspace_bytes(int32_t n, int32_t F, int32_t T);
+int32_t e2eg_block_norms(int32_t n, int32_t dtype, int32_t F, int32_t T, const void* d_G, int64_t ld,
+                         double* d_norms, void* ws, size_t ws_bytes, void* stream);
+int32_t e2eg_gradnorm_step(int32_t T, const double* h_loss, const double* h_loss0, const double* h_gnorm,
+                           double gamma, double lr, double* h_w, double* h_meta_loss);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement aid (not part of the path): per-launch duration of the neighbour-sum kernel, the
  * kernel that moves nearly all bytes of e2eg_propagate_*.  Between e2eg_profile_begin() and
  * e2eg_profile_end() every launch of that kernel made by the calling thread is bracketed by a

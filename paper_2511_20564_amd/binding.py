@@ -49,6 +49,9 @@ SIGNATURES = {
     "e2eg_readout_mean": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
     "e2eg_gfae_loss_workspace_bytes": (_sz, [_i32, _i32]),
     "e2eg_gfae_loss": (_i32, [_i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _sz, _vp]),
+    "e2eg_block_norms_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "e2eg_block_norms": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _vp, _sz, _vp]),
+    "e2eg_gradnorm_step": (_i32, [_i32, _vp, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp]),
     "e2eg_profile_begin": (_i32, [_i32]),
     "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "e2eg_profile_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
@@ -210,3 +213,24 @@ def e2eg_aggregate(mode, n, nnz, d_row_ptr, d_col_idx, d_sched, dtype, F, d_X, l
     _check(load_library().e2eg_aggregate(mode, n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_sched), dtype, F,
                                          _ptr(d_X), ldx, _ptr(d_addend), ld_add, _ptr(d_Y), ldy, _ptr(ws),
                                          _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_block_norms_workspace_bytes(n, F, T) -> int:
+    return int(load_library().e2eg_block_norms_workspace_bytes(n, F, T))
+
+
+def e2eg_block_norms(n, dtype, F, T, d_G, ld, d_norms, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_block_norms(n, dtype, F, T, _ptr(d_G), ld, _ptr(d_norms), _ptr(ws),
+                                           _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_gradnorm_step(loss, loss0, gnorm, w, gamma=1.0, lr=0.025):
+    """Host arrays in (sequences of T floats) -> (meta-loss at `w`, new weights as a list)."""
+    T = len(w)
+    arr = ctypes.c_double * T
+    a_loss, a_loss0, a_gn, a_w = arr(*loss), arr(*loss0), arr(*gnorm), arr(*w)
+    meta = ctypes.c_double(0.0)
+    _check(load_library().e2eg_gradnorm_step(T, ctypes.addressof(a_loss), ctypes.addressof(a_loss0),
+                                             ctypes.addressof(a_gn), gamma, lr, ctypes.addressof(a_w),
+                                             ctypes.addressof(meta)))
+    return meta.value, list(a_w)

@@ -14,11 +14,15 @@
 // bf16) - fewer bytes, and one rounding of Y.
 #include "common.h"
 
+#include <math.h>
+
 namespace e2eg {
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kLossBlocks = 16384;  // partial sums of the loss
+constexpr int kMaxNormBlocks = 8;   // column blocks (tasks) e2eg_block_norms handles at once
+constexpr int kNormBlocks = 4096;   // workgroups of its first pass
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -137,6 +141,62 @@ __global__ __launch_bounds__(kThreads) void gfae_loss_total(const double* __rest
     }
 }
 
+// Partial sums of squares of the T column blocks of g ([n][T * F]); block t of workgroup b goes to
+// partial[b * T + t].  Grid-stride over 16-byte chunks; a chunk never straddles two blocks because F
+// is a multiple of the chunk width.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void block_sumsq_partial(const typename Chunk<BF16>::elem* __restrict__ g,
+                                                                int64_t ld, int64_t n, int32_t F, int32_t T,
+                                                                double* __restrict__ partial) {
+    constexpr int V = Chunk<BF16>::kVec;
+    __shared__ double red[kThreads];
+    const int chunks_per_block = F / V;
+    const int chunks = chunks_per_block * T;
+    const int64_t total = n * chunks;
+    double sum[kMaxNormBlocks];
+#pragma unroll
+    for (int t = 0; t < kMaxNormBlocks; ++t) sum[t] = 0.0;
+    for (int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x; id < total; id += (int64_t)gridDim.x * kThreads) {
+        const int64_t row = id / chunks;
+        const int cidx = (int)(id - row * chunks);
+        const int t = cidx / chunks_per_block;
+        float v[V];
+        Chunk<BF16>::load(g + row * ld + (int64_t)cidx * V, v);
+        double s = 0.0;
+#pragma unroll
+        for (int k = 0; k < V; ++k) s += (double)v[k] * (double)v[k];
+#pragma unroll
+        for (int u = 0; u < kMaxNormBlocks; ++u)
+            if (u == t) sum[u] += s;
+    }
+    for (int t = 0; t < T; ++t) {
+        __syncthreads();
+        red[threadIdx.x] = sum[t];
+        __syncthreads();
+        for (int half = kThreads / 2; half > 0; half >>= 1) {   // fixed pairing: the same tree every run
+            if ((int)threadIdx.x < half) red[threadIdx.x] += red[threadIdx.x + half];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) partial[(int64_t)blockIdx.x * T + t] = red[0];
+    }
+}
+
+// One workgroup per column block t: adds its partials in a fixed order and takes the root.
+__global__ __launch_bounds__(kThreads) void block_norms_total(const double* __restrict__ partial, int32_t count,
+                                                              int32_t T, double* __restrict__ norms) {
+    __shared__ double red[kThreads];
+    const int t = blockIdx.x;
+    double s = 0.0;
+    for (int32_t k = threadIdx.x; k < count; k += kThreads) s += partial[(int64_t)k * T + t];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        for (int k = 0; k < kThreads; ++k) tot += red[k];
+        norms[t] = sqrt(tot);
+    }
+}
+
 int32_t check_shape(const char* who, int32_t n, int32_t dtype, int32_t F) {
     if (n < 0) return fail(E2EG_ERR_INVALID_ARG, "%s: negative size", who);
     if (dtype != E2EG_F32 && dtype != E2EG_BF16) return fail(E2EG_ERR_BAD_DTYPE, "%s: dtype %d", who, dtype);
@@ -233,5 +293,74 @@ extern "C" int32_t e2eg_gfae_loss(int32_t n, int32_t dtype, int32_t F, const voi
     E2EG_LAUNCH_CHECK("gfae_loss_partial");
     gfae_loss_total<<<dim3(1), dim3(kThreads), 0, stream>>>(partial, (int32_t)blocks, d_loss);
     E2EG_LAUNCH_CHECK("gfae_loss_total");
+    return E2EG_OK;
+}
+
+extern "C" size_t e2eg_block_norms_workspace_bytes(int32_t n, int32_t F, int32_t T) {
+    (void)n;
+    (void)F;
+    if (T < 1 || T > kMaxNormBlocks) return 0;
+    return align_up(sizeof(double) * (size_t)kNormBlocks * (size_t)T);
+}
+
+extern "C" int32_t e2eg_block_norms(int32_t n, int32_t dtype, int32_t F, int32_t T, const void* d_G, int64_t ld,
+                                    double* d_norms, void* ws, size_t ws_bytes, void* stream_) {
+    const char* who = "block_norms";
+    int32_t st = check_shape(who, n, dtype, F);
+    if (st != E2EG_OK) return st;
+    if (T < 1 || T > kMaxNormBlocks) return fail(E2EG_ERR_INVALID_ARG, "%s: T=%d must be in [1, %d]", who, T, kMaxNormBlocks);
+    if ((st = check_matrix(who, "d_G", d_G, ld, T * F, dtype)) != E2EG_OK) return st;
+    if (!d_norms) return fail(E2EG_ERR_NULL_PTR, "%s: d_norms is null", who);
+    if (!aligned_to(d_norms, 8)) return fail(E2EG_ERR_INVALID_ARG, "%s: d_norms is not 8-byte aligned", who);
+    const size_t need = e2eg_block_norms_workspace_bytes(n, F, T);
+    if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
+        return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    double* partial = static_cast<double*>(ws);
+    const int vec = dtype == E2EG_F32 ? 4 : 8;
+    const int64_t total = (int64_t)n * (F / vec) * T;
+    int64_t blocks = ceil_div(total, kThreads);
+    if (blocks > kNormBlocks) blocks = kNormBlocks;
+    if (blocks < 1) blocks = 1;
+    const dim3 grid((unsigned)blocks), blk(kThreads);
+    if (dtype == E2EG_F32)
+        block_sumsq_partial<false><<<grid, blk, 0, stream>>>(static_cast<const float*>(d_G), ld, n, F, T, partial);
+    else
+        block_sumsq_partial<true><<<grid, blk, 0, stream>>>(static_cast<const uint16_t*>(d_G), ld, n, F, T, partial);
+    E2EG_LAUNCH_CHECK("block_sumsq_partial");
+    block_norms_total<<<dim3((unsigned)T), blk, 0, stream>>>(partial, (int32_t)blocks, T, d_norms);
+    E2EG_LAUNCH_CHECK("block_norms_total");
+    return E2EG_OK;
+}
+
+// Host arithmetic on T scalars per array: no device work.
+extern "C" int32_t e2eg_gradnorm_step(int32_t T, const double* h_loss, const double* h_loss0,
+                                      const double* h_gnorm, double gamma, double lr, double* h_w,
+                                      double* h_meta_loss) {
+    const char* who = "gradnorm_step";
+    if (T < 1) return fail(E2EG_ERR_INVALID_ARG, "%s: T=%d must be >= 1", who, T);
+    if (!h_loss || !h_loss0 || !h_gnorm || !h_w) return fail(E2EG_ERR_NULL_PTR, "%s: null pointer", who);
+    double gbar = 0.0, rbar = 0.0;
+    for (int32_t i = 0; i < T; ++i) {
+        if (!(h_loss0[i] > 0.0) || !(h_w[i] > 0.0))
+            return fail(E2EG_ERR_INVALID_ARG, "%s: initial losses and weights must be positive", who);
+        gbar += h_w[i] * h_gnorm[i];
+        rbar += h_loss[i] / h_loss0[i];
+    }
+    gbar /= (double)T;
+    rbar /= (double)T;
+    if (!(rbar > 0.0)) return fail(E2EG_ERR_INVALID_ARG, "%s: the mean loss ratio must be positive", who);
+    double meta = 0.0, total = 0.0;
+    for (int32_t i = 0; i < T; ++i) {
+        const double diff = h_w[i] * h_gnorm[i] - gbar * pow(h_loss[i] / h_loss0[i] / rbar, gamma);
+        meta += fabs(diff);
+        const double slope = diff > 0.0 ? h_gnorm[i] : (diff < 0.0 ? -h_gnorm[i] : 0.0);
+        double w = h_w[i] - lr * slope;
+        if (w < 1e-8) w = 1e-8;
+        h_w[i] = w;
+        total += w;
+    }
+    for (int32_t i = 0; i < T; ++i) h_w[i] *= (double)T / total;
+    if (h_meta_loss) *h_meta_loss = meta;
     return E2EG_OK;
 }

@@ -190,3 +190,14 @@ def aggregate(g: Graph, X: torch.Tensor, mode: int, addend: torch.Tensor | None 
     B.e2eg_aggregate(mode, g.n, g.nnz, g.row_ptr, g.col_idx, g.sched, code, F, X, X.stride(0),
                      addend, addend.stride(0) if addend is not None else 0, out, out.stride(0), ws, None, _stream())
     return out
+
+
+def block_norms(G: torch.Tensor, T: int) -> torch.Tensor:
+    """2-norms of the T column blocks of G [n, T*F] as a float64 device tensor of length T."""
+    _require_gpu()
+    n, TF = G.shape
+    assert TF % T == 0 and G.stride(1) == 1
+    norms = torch.empty(T, dtype=torch.float64, device=G.device)
+    ws = _bytes(B.e2eg_block_norms_workspace_bytes(n, TF // T, T), G.device)
+    B.e2eg_block_norms(n, _dtype_code(G), TF // T, T, G, G.stride(0), norms, ws, None, _stream())
+    return norms

@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -194,6 +195,23 @@ def test_readout_and_gfae_argument_errors(B):
         == B.E2EG_ERR_INVALID_ARG                             # ldy < F
     assert status_of(B, g, 10, B.E2EG_BF16, 16, FAKE, 16, FAKE, 16, FAKE, None, 16, 1.0, FAKE, 8) \
         == B.E2EG_ERR_WORKSPACE
+
+
+def test_gradnorm_step_is_host_arithmetic(B, oracle):
+    """e2eg_gradnorm_step needs no GPU: compared with the oracle here, on the CPU."""
+    rng = np.random.default_rng(3)
+    for T in (1, 2, 4):
+        loss, loss0, gn = rng.uniform(0.5, 2, T), rng.uniform(0.5, 2, T), rng.uniform(0.1, 3, T)
+        w0 = rng.uniform(0.5, 1.5, T)
+        meta, w = B.e2eg_gradnorm_step(list(loss), list(loss0), list(gn), list(w0), gamma=1.0, lr=0.05)
+        meta_r, w_r = oracle.gradnorm_step(loss, loss0, gn, w0, gamma=1.0, lr=0.05)
+        assert abs(meta - meta_r) <= 1e-12 * max(1.0, meta_r)
+        assert np.allclose(w, w_r, rtol=1e-12)
+    assert status_of(B, B.e2eg_gradnorm_step, [1.0], [0.0], [1.0], [1.0]) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_block_norms, 10, B.E2EG_F32, 8, 9, FAKE, 72, FAKE, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_block_norms, 10, B.E2EG_F32, 8, 2, FAKE, 8, FAKE, FAKE, 1 << 20) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_block_norms, 10, B.E2EG_F32, 8, 2, FAKE, 16, None, FAKE, 1 << 20) == B.E2EG_ERR_NULL_PTR
+    assert B.e2eg_block_norms_workspace_bytes(10, 8, 2) > 0 and B.e2eg_block_norms_workspace_bytes(10, 8, 9) == 0
 
 
 def test_profile_aid_rejects_bad_arguments(B):

@@ -113,3 +113,33 @@ def test_two_upstream_gradients_in_one_pass(dev, oracle):
         ref = oracle.propagate_bwd(row_ptr, col, src, K)
         sc = oracle.propagate_bwd(row_ptr, col, np.abs(oracle.as_f64(src)), K)
         assert_close(to_f64(half), ref, sc, dt, "stacked backward")
+
+
+@pytest.mark.parametrize("dtype,F,T", [("f32", 8, 1), ("f32", 64, 2), ("bf16", 128, 2), ("bf16", 16, 8)])
+def test_block_norms(dev, oracle, dtype, F, T):
+    from workloads import make_features
+    n = 30_011
+    G = make_features(n, T * F, 1.0, 9, dtype)
+    got = dev.block_norms(to_device(G, dtype), T).cpu().numpy()
+    ref = oracle.block_norms(G, T)
+    assert np.allclose(got, ref, rtol=1e-12)
+    again = dev.block_norms(to_device(G, dtype), T).cpu().numpy()
+    assert np.array_equal(got, again)
+
+
+def test_gradnorm_iteration_on_the_gpu_gradients(dev, oracle):
+    """One weight update from real gradients: two upstream gradients through one stacked
+    backward, block norms on the GPU, the scalar step in the library; against the oracle chain."""
+    c = make_config(2, scale=0.2)
+    K, dt, F = c["K"], c["dtype"], c["F"]
+    g = dev.build_graph(c["n_users"], c["n_items"], torch.from_numpy(c["users"]).cuda(), torch.from_numpy(c["items"]).cuda())
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    up = np.concatenate([c["gY"], 0.3 * c["X0"]], axis=1).astype(np.float32)
+    G = dev.propagate_bwd(g, to_device(up, dt), K)
+    norms = dev.block_norms(G, 2).cpu().numpy()
+    ref = oracle.block_norms(np.concatenate([oracle.propagate_bwd(row_ptr, col, up[:, :F], K),
+                                             oracle.propagate_bwd(row_ptr, col, up[:, F:], K)], axis=1), 2)
+    assert np.allclose(norms, ref, rtol=1e-5)
+    meta, w = dev.B.e2eg_gradnorm_step([0.8, 1.7], [1.0, 2.0], list(norms), [1.0, 1.0], gamma=1.0, lr=0.025)
+    meta_r, w_r = oracle.gradnorm_step([0.8, 1.7], [1.0, 2.0], ref, [1.0, 1.0], gamma=1.0, lr=0.025)
+    assert abs(meta - meta_r) <= 1e-4 * meta_r and np.allclose(w, w_r, rtol=1e-4)
