@@ -321,7 +321,7 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
 }
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
-constexpr int kShortPerWave = 16;  // short rows a wavefront works through, 64/G at a time
+constexpr int kShortPerWave = 8;   // short rows a wavefront works through, 64/G at a time
 constexpr int kSingleBlocksPerXcd = 512;
 
 // Three kinds of workgroup.
