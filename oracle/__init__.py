@@ -54,6 +54,12 @@ def _load():
                                                    _f64p, _f64p]
         lib.e2eg_oracle_mean_neighbours.argtypes = [ctypes.c_int64, _i64p, _i32p, ctypes.c_int64, _f64p, _f64p]
         lib.e2eg_oracle_mean_neighbours_transposed.argtypes = lib.e2eg_oracle_mean_neighbours.argtypes
+        lib.e2eg_oracle_edge_values.argtypes = [ctypes.c_int32, ctypes.c_int64, _i32p, _i32p, _f64p, ctypes.c_int64,
+                                                _i64p, _i32p, _f64p]
+        lib.e2eg_oracle_weighted_degrees.argtypes = [ctypes.c_int64, _i64p, _f64p, _f64p]
+        lib.e2eg_oracle_propagate_layer_weighted.argtypes = [ctypes.c_int64, _i64p, _i32p, _f64p, _f64p, ctypes.c_int64,
+                                                             _f64p, _f64p]
+        lib.e2eg_oracle_propagate_layer_weighted_transposed.argtypes = lib.e2eg_oracle_propagate_layer_weighted.argtypes
         lib.e2eg_oracle_block_norms.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _f64p, _f64p]
         lib.e2eg_oracle_gradnorm_step.restype = ctypes.c_double
         lib.e2eg_oracle_gradnorm_step.argtypes = [ctypes.c_int64, _f64p, _f64p, _f64p, ctypes.c_double, ctypes.c_double,
@@ -311,3 +317,42 @@ def gradnorm_step(loss, loss0, gnorm, w, gamma=1.0, lr=0.025):
     meta = _load().e2eg_oracle_gradnorm_step(w.size, _p(loss, _f64p), _p(loss0, _f64p), _p(gnorm, _f64p),
                                              float(gamma), float(lr), _p(w, _f64p))
     return float(meta), w
+
+
+def edge_values(n_users, users, items, weights, row_ptr, col_idx):
+    """Values of the stored entries of the weighted A~: 1 on the diagonal, the edge weight both
+    ways; a repeated pair keeps its largest weight."""
+    users, items = _c(users, np.int32), _c(items, np.int32)
+    weights = _c(weights, np.float64)
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    val = np.empty(col_idx.size, dtype=np.float64)
+    _load().e2eg_oracle_edge_values(n_users, users.size, _p(users, _i32p), _p(items, _i32p), _p(weights, _f64p),
+                                    row_ptr.size - 1, _p(row_ptr, _i64p), _p(col_idx, _i32p), _p(val, _f64p))
+    return val
+
+
+def weighted_degrees(row_ptr, val):
+    row_ptr, val = _c(row_ptr, np.int64), _c(val, np.float64)
+    deg = np.empty(row_ptr.size - 1, dtype=np.float64)
+    _load().e2eg_oracle_weighted_degrees(deg.size, _p(row_ptr, _i64p), _p(val, _f64p), _p(deg, _f64p))
+    return deg
+
+
+def propagate_layer_weighted(row_ptr, col_idx, val, X, transposed=False):
+    """A^ X (or A^T X) for the weighted operator A^_ij = val_ij / sqrt(d~_i d~_j)."""
+    row_ptr, col_idx, val = _c(row_ptr, np.int64), _c(col_idx, np.int32), _c(val, np.float64)
+    X = as_f64(X)
+    n, F = X.shape
+    deg = weighted_degrees(row_ptr, val)
+    Y = np.empty_like(X)
+    fn = _load().e2eg_oracle_propagate_layer_weighted_transposed if transposed else _load().e2eg_oracle_propagate_layer_weighted
+    fn(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), _p(val, _f64p), _p(deg, _f64p), F, _p(X, _f64p), _p(Y, _f64p))
+    return Y
+
+
+def propagate_weighted(row_ptr, col_idx, val, X0, K, transposed=False):
+    """K layers of the weighted operator (forward: A^, backward: A^T); -> the last layer."""
+    H = as_f64(X0)
+    for _ in range(K):
+        H = propagate_layer_weighted(row_ptr, col_idx, val, H, transposed)
+    return H

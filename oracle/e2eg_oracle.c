@@ -26,6 +26,9 @@
  *   - Layer combination of LightGCN, Y = 1/(L+1) sum_{l=0..L} H(l) (Section 3.1, the final
  *     representation as the mean of all layers), and the GFAE reconstruction loss with the
  *     identity decoder, L_ssl = ||X - Y||_F^2 (Section 4.2), with dL/dY = 2 (Y - X).
+ *   - Weighted graphs (Section 3, "Notation": A_ij > 0 iff (i,j) in E, D = diag(A 1)): with real
+ *     edge weights the same definitions give d~_i = 1 + sum_j A_ij and A^_ij = A~_ij / sqrt(d~_i d~_j),
+ *     the self-loop weighing 1.  A pair given several times carries the largest of its weights.
  *   - GraphSAGE layer (Section 3.1): mean of the neighbours' rows, hbar_u = 1/|S(u)| sum_{v in S(u)} h_v
  *     with S(u) the node's neighbours in the given (sampled) graph, then
  *     h'_u = sigma(W . CONCAT(h_u, hbar_u)); sigma = ReLU here.
@@ -324,4 +327,67 @@ double e2eg_oracle_gradnorm_step(int64_t T, const double* loss, const double* lo
     }
     for (int64_t i = 0; i < T; ++i) w[i] *= (double)T / sum;
     return meta;
+}
+
+/*
+ * Values of the stored entries of a weighted A~ on the structure made by e2eg_oracle_build_csr:
+ * val = 1 on the diagonal, the edge weight on (u, nu+i) and (nu+i, u); a pair listed several times
+ * gets the largest of its weights.  Entries are found by scanning the row.
+ */
+void e2eg_oracle_edge_values(int32_t n_users, int64_t n_edges, const int32_t* users, const int32_t* items,
+                             const double* weights, int64_t n, const int64_t* row_ptr, const int32_t* col_idx,
+                             double* val) {
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) val[p] = col_idx[p] == i ? 1.0 : 0.0;
+    for (int64_t e = 0; e < n_edges; ++e) {
+        int64_t a = users[e], b = (int64_t)n_users + items[e];
+        for (int dir = 0; dir < 2; ++dir) {
+            int64_t r = dir ? b : a, c = dir ? a : b;
+            for (int64_t p = row_ptr[r]; p < row_ptr[r + 1]; ++p)
+                if (col_idx[p] == c && weights[e] > val[p]) val[p] = weights[e];
+        }
+    }
+}
+
+/* d~_i = sum_j A~_ij with the stored values (Section 3: D~ = D + I, D = diag(A 1)). */
+void e2eg_oracle_weighted_degrees(int64_t n, const int64_t* row_ptr, const double* val, double* deg) {
+    for (int64_t i = 0; i < n; ++i) {
+        double d = 0.0;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) d += val[p];
+        deg[i] = d;
+    }
+}
+
+/* Y = A^ X with A^_ij = val_ij / sqrt(d~_i d~_j), d~ from the stored values (a row of zero sum gives 0). */
+void e2eg_oracle_propagate_layer_weighted(int64_t n, const int64_t* row_ptr, const int32_t* col_idx,
+                                          const double* val, const double* deg, int64_t F, const double* X,
+                                          double* Y) {
+    for (int64_t i = 0; i < n; ++i) {
+        double* y = Y + i * F;
+        for (int64_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            double den = sqrt(deg[i] * deg[j]);
+            double a = den > 0.0 ? val[p] / den : 0.0;
+            const double* x = X + j * F;
+            for (int64_t f = 0; f < F; ++f) y[f] += a * x[f];
+        }
+    }
+}
+
+/* G = A^T Gnext for the weighted operator, scatter form over the same CSR. */
+void e2eg_oracle_propagate_layer_weighted_transposed(int64_t n, const int64_t* row_ptr, const int32_t* col_idx,
+                                                     const double* val, const double* deg, int64_t F,
+                                                     const double* Gnext, double* G) {
+    for (int64_t k = 0; k < n * F; ++k) G[k] = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const double* g = Gnext + i * F;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            double den = sqrt(deg[i] * deg[j]);
+            double a = den > 0.0 ? val[p] / den : 0.0;
+            double* o = G + j * F;
+            for (int64_t f = 0; f < F; ++f) o[f] += a * g[f];
+        }
+    }
 }

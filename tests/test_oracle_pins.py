@@ -656,3 +656,52 @@ def test_block_norms_match_numpy(oracle):
     G = np.random.default_rng(5).standard_normal((37, 12))
     got = oracle.block_norms(G, 3)
     assert np.allclose(got, [np.linalg.norm(G[:, 4 * t:4 * t + 4]) for t in range(3)], rtol=1e-14)
+
+
+# ---------------------------------------------------------------- weighted graphs
+def dense_weighted_ahat(nu, ni, u, i, w):
+    """A^ from Section 3 "Notation" with real weights: A_ij = weight, A~ = A + I, D~ = D + I."""
+    n = nu + ni
+    A = np.zeros((n, n))
+    for a, b, x in zip(u, i, w):
+        A[a, nu + b] = max(A[a, nu + b], x)          # a repeated pair keeps its largest weight
+        A[nu + b, a] = A[a, nu + b]
+    At = A + np.eye(n)
+    d = A.sum(1) + 1.0
+    return np.diag(d ** -0.5) @ At @ np.diag(d ** -0.5), d
+
+
+def test_weighted_operator_matches_dense(oracle):
+    nu, ni, u, i = small_graph(12)
+    w = np.random.default_rng(12).uniform(0.1, 3.0, size=u.size)
+    Ahat, d = dense_weighted_ahat(nu, ni, u, i, w)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    val = oracle.edge_values(nu, u, i, w, row_ptr, col)
+    assert np.allclose(oracle.weighted_degrees(row_ptr, val), d, rtol=1e-14)
+    X = np.random.default_rng(1).standard_normal((nu + ni, 4))
+    assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, X), Ahat @ X) < 1e-13
+    assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, X, transposed=True), Ahat.T @ X) < 1e-13
+    assert relerr(oracle.propagate_weighted(row_ptr, col, val, X, 3), np.linalg.matrix_power(Ahat, 3) @ X) < 1e-12
+    # invariants of the weighted operator: symmetric, D~^1/2 1 a fixed point, spectrum in (-1, 1]
+    assert np.allclose(Ahat, Ahat.T)
+    r = np.sqrt(d)[:, None]
+    assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, r), r) < 1e-13
+    ev = np.linalg.eigvalsh(Ahat)
+    assert ev.max() <= 1 + 1e-12 and ev.min() > -1
+    # slips: weights ignored, degrees counted instead of summed, self-loop weighted like an edge
+    Au, _ = dense_ahat(nu, ni, u, i)
+    assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, X), Au @ X) > 1e-3
+
+
+def test_weighted_single_edge_closed_form_and_unit_weights(oracle):
+    # one edge of weight w: d~ = 1 + w on both ends, A^ = [[1, w], [w, 1]] / (1 + w)
+    row_ptr, col = oracle.build_csr(1, 1, np.array([0], np.int32), np.array([0], np.int32))
+    val = oracle.edge_values(1, [0], [0], [3.0], row_ptr, col)
+    M = oracle.propagate_layer_weighted(row_ptr, col, val, np.eye(2))
+    assert np.allclose(M, np.array([[1.0, 3.0], [3.0, 1.0]]) / 4.0, rtol=1e-15)
+    # all weights 1: the unweighted operator
+    nu, ni, u, i = small_graph(5)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    val = oracle.edge_values(nu, u, i, np.ones(u.size), row_ptr, col)
+    X = np.random.default_rng(2).standard_normal((nu + ni, 3))
+    assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, X), oracle.propagate_layer(row_ptr, col, X)) < 1e-14
