@@ -233,6 +233,51 @@ int32_t e2eg_gradnorm_step(int32_t T, const double* h_loss, const double* h_loss
                            double gamma, double lr, double* h_w, double* h_meta_loss);
 
 /* ------------------------------------------------------------------------------------------
+ * Weighted graphs: A_ij is the strength of edge (i,j) instead of 1 (Section 3, "Notation": A is
+ * nonnegative and A_ij > 0 marks an edge; D = diag(A 1), D~ = D + I, A^ = D~^-1/2 (A + I) D~^-1/2).
+ * The structure is the one e2eg_build_csr makes (with E2EG_ADD_SELF_LOOPS); the values live in a
+ * float array d_val[nnz] beside d_col_idx.
+ *
+ * e2eg_edge_weights: fills d_val for the CSR that e2eg_build_csr made from the same pairs:
+ * 1 on every diagonal entry, d_weights[e] on the two entries of pair e; a pair listed several
+ * times keeps the largest of its weights (the reading taken here: the structure already treats
+ * repeats as one edge).  A weight that is not > 0 (NaN included) is ignored, and so is a pair whose
+ * ids are out of range or that the CSR does not hold; an entry that no pair reaches stays 0.
+ * Integer atomics only: the result does not depend on the order of the pairs.  Does not wait.
+ *
+ * e2eg_normalize_weighted: e2eg_normalize for such a graph.  d_deg_w[i] (may be NULL) = d~_i =
+ * the sum of row i of d_val, added in double in a fixed order; d_dinv_sqrt[i] = (float)(1 /
+ * sqrt(d~_i)), 0 where the sum is not positive.  d_sched needs e2eg_sched_weighted_bytes(n, nnz)
+ * bytes: the unweighted schedule followed by the values in the library's own entry order.  Each
+ * row must hold a column at most once (a repeat leaves one of the values out).  The workspace is
+ * that of e2eg_normalize.
+ *
+ * e2eg_propagate_weighted_fwd / _bwd: e2eg_propagate_fwd / _bwd, argument for argument, on a
+ * schedule made by e2eg_normalize_weighted; each gathered row is multiplied by its entry's value
+ * (fp32 fused multiply-add).  The backward pass applies the same operator, so the values must
+ * be symmetric, val(i,j) = val(j,i), which e2eg_edge_weights guarantees; this is not checked.
+ * Passing a schedule of the other kind to either family is an error the library cannot detect.
+ */
+int32_t e2eg_edge_weights(int32_t n_users, int32_t n_items, int64_t n_edges, const int32_t* d_user_ids,
+                          const int32_t* d_item_ids, const float* d_weights, int64_t nnz,
+                          const int32_t* d_row_ptr, const int32_t* d_col_idx, float* d_val, void* stream);
+size_t e2eg_sched_weighted_bytes(int32_t n, int64_t nnz);
+int32_t e2eg_normalize_weighted(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                                const float* d_val, float* d_deg_w, float* d_dinv_sqrt, void* d_sched,
+                                size_t sched_bytes, void* ws, size_t ws_bytes, void* stream);
+int32_t e2eg_propagate_weighted_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                    const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                    const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                    const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
+                                    int64_t layer_stride, void* ws, size_t ws_bytes, void* stream);
+int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                    const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                    const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                    const void* d_gXK, int64_t ldg, const void* d_gLayers,
+                                    int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                                    size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement aid (not part of the path): per-launch duration of the neighbour-sum kernel, the
  * kernel that moves nearly all bytes of e2eg_propagate_*.  Between e2eg_profile_begin() and
  * e2eg_profile_end() every launch of that kernel made by the calling thread is bracketed by a

@@ -52,6 +52,11 @@ SIGNATURES = {
     "e2eg_block_norms_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "e2eg_block_norms": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _vp, _sz, _vp]),
     "e2eg_gradnorm_step": (_i32, [_i32, _vp, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp]),
+    "e2eg_edge_weights": (_i32, [_i32, _i32, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp]),
+    "e2eg_sched_weighted_bytes": (_sz, [_i32, _i64]),
+    "e2eg_normalize_weighted": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_propagate_weighted_fwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "e2eg_propagate_weighted_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_profile_begin": (_i32, [_i32]),
     "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "e2eg_profile_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
@@ -160,6 +165,42 @@ def e2eg_propagate_bwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype
                                              _ptr(d_sched), dtype, F, K, _ptr(d_gXK), ldg, _ptr(d_gLayers),
                                              g_layer_stride, _ptr(d_gX0), ldo, _ptr(ws),
                                              _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_edge_weights(n_users, n_items, n_edges, d_user_ids, d_item_ids, d_weights, nnz, d_row_ptr, d_col_idx,
+                      d_val, stream=0):
+    _check(load_library().e2eg_edge_weights(n_users, n_items, n_edges, _ptr(d_user_ids), _ptr(d_item_ids),
+                                            _ptr(d_weights), nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_val),
+                                            stream or None))
+
+
+def e2eg_sched_weighted_bytes(n, nnz) -> int:
+    return int(load_library().e2eg_sched_weighted_bytes(n, nnz))
+
+
+def e2eg_normalize_weighted(n, nnz, d_row_ptr, d_col_idx, d_val, d_deg_w, d_dinv_sqrt, d_sched, sched_bytes, ws,
+                            ws_bytes=None, stream=0):
+    _check(load_library().e2eg_normalize_weighted(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_val),
+                                                  _ptr(d_deg_w), _ptr(d_dinv_sqrt), _ptr(d_sched),
+                                                  _nbytes(d_sched) if sched_bytes is None else sched_bytes,
+                                                  _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                                  stream or None))
+
+
+def e2eg_propagate_weighted_fwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_X0, ldx, d_Xout,
+                                ldo, layer_stride, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_propagate_weighted_fwd(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_dinv_sqrt),
+                                                      _ptr(d_sched), dtype, F, K, _ptr(d_X0), ldx, _ptr(d_Xout),
+                                                      ldo, layer_stride, _ptr(ws),
+                                                      _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_propagate_weighted_bwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_gXK, ldg,
+                                d_gLayers, g_layer_stride, d_gX0, ldo, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_propagate_weighted_bwd(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_dinv_sqrt),
+                                                      _ptr(d_sched), dtype, F, K, _ptr(d_gXK), ldg, _ptr(d_gLayers),
+                                                      g_layer_stride, _ptr(d_gX0), ldo, _ptr(ws),
+                                                      _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
 
 
 def e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype) -> int:

@@ -99,6 +99,45 @@ __global__ void fill_diagonal(const int32_t* __restrict__ row_ptr, int64_t n, in
     col_idx[at] = (int32_t)v;
 }
 
+// Weighted graphs (Section 3, "Notation": A_ij > 0 marks an edge, so its size is free to carry
+// a strength).  Stored values of A~: 1 on the diagonal, 0 until a listed pair brings its weight.
+__global__ void init_values(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                            int64_t n, int64_t nnz, float* __restrict__ val) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    int64_t lo = 0, hi = n - 1;  // the row of entry e: last i with row_ptr[i] <= e
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    val[e] = col_idx[e] == (int32_t)lo ? 1.0f : 0.0f;
+}
+
+// One thread per (pair, direction): the entry is found by binary search in its (ascending) row; a
+// pair listed several times keeps its largest weight.  Positive floats order like their bit
+// patterns read as integers, which makes the maximum an integer atomic and the result independent
+// of the order of arrival.
+__global__ void apply_weights(const int32_t* __restrict__ users, const int32_t* __restrict__ items,
+                              const float* __restrict__ weights, int64_t n_edges, int32_t n_users,
+                              int32_t n_items, const int32_t* __restrict__ row_ptr,
+                              const int32_t* __restrict__ col_idx, float* val) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= 2 * n_edges) return;
+    const int64_t e = t >> 1;
+    const int32_t u = users[e], i = items[e];
+    const float w = weights[e];
+    if (u < 0 || u >= n_users || i < 0 || i >= n_items || !(w > 0.0f)) return;
+    const int32_t r = (t & 1) ? n_users + i : u;
+    const int32_t c = (t & 1) ? u : n_users + i;
+    const int32_t end = row_ptr[r + 1];
+    int32_t lo = row_ptr[r], hi = end;  // first position with col_idx >= c
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (col_idx[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    if (lo < end && col_idx[lo] == c) atomicMax(reinterpret_cast<int*>(val) + lo, __float_as_int(w));
+}
+
 struct BuildWs {
     uint64_t* buf_a;
     uint64_t* buf_b;
@@ -224,6 +263,31 @@ extern "C" int32_t e2eg_build_csr(int32_t n_users, int32_t n_items, int64_t n_ed
     if (self && n > 0) {
         fill_diagonal<<<dim3(blocks_for(n, kThreads)), blk, 0, stream>>>(d_row_ptr, n, n_users, d_col_idx);
         E2EG_LAUNCH_CHECK("fill_diagonal");
+    }
+    return E2EG_OK;
+}
+
+extern "C" int32_t e2eg_edge_weights(int32_t n_users, int32_t n_items, int64_t n_edges,
+                                     const int32_t* d_user_ids, const int32_t* d_item_ids,
+                                     const float* d_weights, int64_t nnz, const int32_t* d_row_ptr,
+                                     const int32_t* d_col_idx, float* d_val, void* stream_) {
+    if (n_users < 0 || n_items < 0 || n_edges < 0 || nnz < 0)
+        return fail(E2EG_ERR_INVALID_ARG, "edge_weights: negative size");
+    const int64_t n = (int64_t)n_users + n_items;
+    if (n > INT32_MAX - 1 || n_edges > (int64_t)INT32_MAX || nnz > (int64_t)INT32_MAX)
+        return fail(E2EG_ERR_OVERFLOW, "edge_weights: n=%lld, nnz=%lld exceed int32", (long long)n, (long long)nnz);
+    if (!d_row_ptr || (n_edges > 0 && (!d_user_ids || !d_item_ids || !d_weights)) || (nnz > 0 && (!d_col_idx || !d_val)))
+        return fail(E2EG_ERR_NULL_PTR, "edge_weights: null pointer");
+    if (nnz > 0 && n == 0) return fail(E2EG_ERR_INVALID_ARG, "edge_weights: entries given but no nodes");
+    if (nnz == 0) return E2EG_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const dim3 blk(kThreads);
+    init_values<<<dim3(blocks_for(nnz, kThreads)), blk, 0, stream>>>(d_row_ptr, d_col_idx, n, nnz, d_val);
+    E2EG_LAUNCH_CHECK("init_values");
+    if (n_edges > 0) {
+        apply_weights<<<dim3(blocks_for(2 * n_edges, kThreads)), blk, 0, stream>>>(
+            d_user_ids, d_item_ids, d_weights, n_edges, n_users, n_items, d_row_ptr, d_col_idx, d_val);
+        E2EG_LAUNCH_CHECK("apply_weights");
     }
     return E2EG_OK;
 }

@@ -133,6 +133,7 @@ struct SchedView {
     int32_t* slot_base;   // [max_multi] first slot of each such row
     int32_t* slot_cnt;    // [max_multi] number of slots
     Segment* segs;        // [max_seg]: slotted segments ordered by first column, then one-segment rows
+    float* zval;          // [nnz] entry values in zcol order (weighted schedules only, else null)
     int64_t max_plain, max_seg, max_multi, max_slot;
 };
 
@@ -150,6 +151,6 @@ inline int64_t sched_max_slot(int64_t n, int64_t nnz) {
     return nnz / kSegLen + sched_max_multi(nnz) + sched_max_pairs(n) + 1;
 }
 inline int64_t sched_max_seg(int64_t n, int64_t nnz) { return sched_max_slot(n, nnz) + sched_max_plain(nnz); }
-size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view);
+size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view, bool weighted = false);
 
 }  // namespace e2eg

@@ -275,6 +275,51 @@ __global__ void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, i
     if (e < nnz) zcol[e] = (int32_t)(keys[e] & ((1ull << bits) - 1));
 }
 
+// Weighted graphs.  d~_i = sum of the stored values of row i (the diagonal entry carries the 1 of
+// D~ = D + I); one wavefront per row, lanes stride over the row, lane sums added in lane order.
+__global__ __launch_bounds__(kThreads) void weighted_degrees(const int32_t* __restrict__ row_ptr,
+                                                             const float* __restrict__ val, int64_t n,
+                                                             float* __restrict__ deg_w,
+                                                             float* __restrict__ dinv_sqrt) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
+    if (row >= n) return;
+    const int32_t beg = row_ptr[row], end = row_ptr[row + 1];
+    double s = 0.0;
+    for (int32_t p = beg + lane; p < end; p += 64) s += (double)val[p];
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);   // fixed tree
+    if (lane == 0) {
+        if (deg_w) deg_w[row] = (float)s;
+        dinv_sqrt[row] = s > 0.0 ? (float)(1.0 / sqrt(s)) : 0.0f;
+    }
+}
+
+// One thread per stored entry e of the caller's CSR: its value goes to the place of the same entry
+// in the internal CSR (row zpos[i], column zpos[j], found by binary search in that row).
+__global__ void place_values(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                             const float* __restrict__ val, int64_t n, int64_t nnz, SchedView s) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    int64_t lo = 0, hi = n - 1;  // last i with row_ptr[i] <= e
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    const int32_t p = s.zpos[lo];
+    const int32_t c = s.zpos[col_idx[e]];
+    int32_t a = s.zrow_ptr[p], b = s.zrow_ptr[p + 1];   // first position with zcol >= c
+    while (a < b) {
+        const int32_t mid = a + ((b - a) >> 1);
+        if (s.zcol[mid] < c) a = mid + 1; else b = mid;
+    }
+    if (a < s.zrow_ptr[p + 1] && s.zcol[a] == c) s.zval[a] = val[e];
+}
+
+__global__ void zero_values(float* __restrict__ v, int64_t count) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < count) v[e] = 0.0f;
+}
+
 struct NormWs {
     uint64_t* keys_a;
     uint64_t* keys_b;
@@ -331,23 +376,31 @@ extern "C" size_t e2eg_sched_bytes(int32_t n, int64_t nnz) {
     return sched_carve(nullptr, n, nnz, nullptr);
 }
 
+extern "C" size_t e2eg_sched_weighted_bytes(int32_t n, int64_t nnz) {
+    if (n < 0 || nnz < 0) return 0;
+    return sched_carve(nullptr, n, nnz, nullptr, true);
+}
+
 extern "C" size_t e2eg_normalize_workspace_bytes(int32_t n, int64_t nnz) {
     if (n < 0 || nnz < 0) return 0;
     return carve_norm(nullptr, n, nnz).bytes;
 }
 
-extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
-                                  const int32_t* d_col_idx, int32_t* d_deg, float* d_dinv_sqrt,
-                                  void* d_sched, size_t sched_bytes, void* ws, size_t ws_bytes,
-                                  void* stream_) {
+namespace {
+// d_val == nullptr: the unweighted call.  Otherwise d~ and d~^-1/2 come from the values (d_deg_w may
+// be null), d_deg is not written, and the schedule also receives the values in internal order.
+int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                       const float* d_val, int32_t* d_deg, float* d_deg_w, float* d_dinv_sqrt, void* d_sched,
+                       size_t sched_bytes, void* ws, size_t ws_bytes, void* stream_) {
+    const bool weighted = d_val != nullptr;
     if (n < 0 || nnz < 0) return fail(E2EG_ERR_INVALID_ARG, "normalize: negative size");
     if (nnz > (int64_t)INT32_MAX || n == INT32_MAX)
         return fail(E2EG_ERR_OVERFLOW, "normalize: nnz=%lld exceeds int32", (long long)nnz);
     if (!d_row_ptr || !d_dinv_sqrt || !d_sched || (nnz > 0 && !d_col_idx))
         return fail(E2EG_ERR_NULL_PTR, "normalize: null pointer");
-    if (!aligned_to(d_sched, kAlign) || sched_bytes < e2eg_sched_bytes(n, nnz))
-        return fail(E2EG_ERR_CAPACITY, "normalize: d_sched needs %zu bytes, 256-byte aligned",
-                    e2eg_sched_bytes(n, nnz));
+    const size_t sched_need = sched_carve(nullptr, n, nnz, nullptr, weighted);
+    if (!aligned_to(d_sched, kAlign) || sched_bytes < sched_need)
+        return fail(E2EG_ERR_CAPACITY, "normalize: d_sched needs %zu bytes, 256-byte aligned", sched_need);
     const size_t need = e2eg_normalize_workspace_bytes(n, nnz);
     if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
         return fail(E2EG_ERR_WORKSPACE, "normalize: workspace needs %zu bytes, 256-byte aligned", need);
@@ -355,7 +408,7 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     NormWs w = carve_norm(ws, n, nnz);
     SchedView view;
-    sched_carve(d_sched, n, nnz, &view);
+    sched_carve(d_sched, n, nnz, &view, weighted);
     const dim3 blk(kThreads);
 
     // 1. degrees, d^-1/2, popularity order, internal numbering
@@ -437,5 +490,38 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
         deal_segments<<<grid_for(view.max_slot + 1), blk, 0, stream>>>(w.seg_len, view);
         E2EG_LAUNCH_CHECK("deal_segments");
     }
+    // 4. weighted graphs: d~ from the values, and the values in internal order
+    if (weighted) {
+        if (n > 0) {
+            weighted_degrees<<<grid_for((int64_t)n * 64), blk, 0, stream>>>(d_row_ptr, d_val, n, d_deg_w, d_dinv_sqrt);
+            E2EG_LAUNCH_CHECK("weighted_degrees");
+        }
+        if (nnz > 0) {
+            // a row that lists a column twice leaves the extra places at zero (see the header)
+            zero_values<<<grid_for(nnz), blk, 0, stream>>>(view.zval, nnz);
+            E2EG_LAUNCH_CHECK("zero_values");
+            place_values<<<grid_for(nnz), blk, 0, stream>>>(d_row_ptr, d_col_idx, d_val, n, nnz, view);
+            E2EG_LAUNCH_CHECK("place_values");
+        }
+    }
     return E2EG_OK;
+}
+}  // namespace
+
+extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                  const int32_t* d_col_idx, int32_t* d_deg, float* d_dinv_sqrt,
+                                  void* d_sched, size_t sched_bytes, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    return normalize_impl(n, nnz, d_row_ptr, d_col_idx, nullptr, d_deg, nullptr, d_dinv_sqrt, d_sched, sched_bytes, ws,
+                          ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_normalize_weighted(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                           const int32_t* d_col_idx, const float* d_val, float* d_deg_w,
+                                           float* d_dinv_sqrt, void* d_sched, size_t sched_bytes, void* ws,
+                                           size_t ws_bytes, void* stream) {
+    if (!d_val && nnz > 0) return fail(E2EG_ERR_NULL_PTR, "normalize_weighted: d_val is null");
+    static const float kOne = 1.0f;  // nnz == 0: any non-null pointer selects the weighted layout
+    return normalize_impl(n, nnz, d_row_ptr, d_col_idx, d_val ? d_val : &kOne, nullptr, d_deg_w, d_dinv_sqrt, d_sched,
+                          sched_bytes, ws, ws_bytes, stream);
 }

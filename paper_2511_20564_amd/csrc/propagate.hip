@@ -143,12 +143,30 @@ struct Sum {
             acc[6] += __uint_as_float(q.w << 16); acc[7] += __uint_as_float(q.w & 0xffff0000u);
         }
     }
+    // acc += w * chunk (weighted graphs: w is the value of the CSR entry)
+    __device__ __forceinline__ void add_scaled(const uint4 q, const float w) {
+        if constexpr (std::is_same<T, F32>::value) {
+            acc[0] = fmaf(w, __uint_as_float(q.x), acc[0]); acc[1] = fmaf(w, __uint_as_float(q.y), acc[1]);
+            acc[2] = fmaf(w, __uint_as_float(q.z), acc[2]); acc[3] = fmaf(w, __uint_as_float(q.w), acc[3]);
+        } else {
+            acc[0] = fmaf(w, __uint_as_float(q.x << 16), acc[0]); acc[1] = fmaf(w, __uint_as_float(q.x & 0xffff0000u), acc[1]);
+            acc[2] = fmaf(w, __uint_as_float(q.y << 16), acc[2]); acc[3] = fmaf(w, __uint_as_float(q.y & 0xffff0000u), acc[3]);
+            acc[4] = fmaf(w, __uint_as_float(q.z << 16), acc[4]); acc[5] = fmaf(w, __uint_as_float(q.z & 0xffff0000u), acc[5]);
+            acc[6] = fmaf(w, __uint_as_float(q.w << 16), acc[6]); acc[7] = fmaf(w, __uint_as_float(q.w & 0xffff0000u), acc[7]);
+        }
+    }
     // `live` of the U gathered chunks q[0..U) are valid (wave-uniform count)
     template <int U>
     __device__ __forceinline__ void add_batch(const uint4 (&q)[U], int live) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (u < live) add(q[u]);
+    }
+    template <int U>
+    __device__ __forceinline__ void add_batch_scaled(const uint4 (&q)[U], const float (&w)[U], int live) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < live) add_scaled(q[u], w[u]);
     }
     // -> out[] = the chunk's total over the lane groups, valid in lanes of group 0
     template <int LOG_G>
@@ -204,7 +222,7 @@ constexpr int kInFlight = 8;  // independent 16-byte gathers in flight per lane
 // indices are fetched 64 at a time, one coalesced load, the next 64 requested before the current
 // gathers are consumed.  slot >= 0: the sum goes to that partial-sum slot; slot < 0: the segment is
 // the whole row and the row is finished here.
-template <typename T, int LOG_G, bool NARROW>
+template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
 __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment seg, const int lane) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
@@ -221,6 +239,9 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
         s = a.dinv_sqrt[node];
     }
     const int32_t idx_first = lane < seg.end - seg.beg ? __builtin_nontemporal_load(a.sched.zcol + seg.beg + lane) : a.n;
+    float wgt_first = 0.0f;  // WEIGHTED: the entries' values travel with their column indices
+    if constexpr (WEIGHTED)
+        if (lane < seg.end - seg.beg) wgt_first = __builtin_nontemporal_load(a.sched.zval + seg.beg + lane);
 
     for (int cb = 0; cb < chunks; cb += G) {   // more than one pass only for rows wider than 1 KiB
         const int cc = cb + c;
@@ -229,29 +250,45 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
         Sum<T> sum;
         sum.clear();
         int32_t idx = idx_first;
+        float wgt = wgt_first;
         for (int32_t base = seg.beg; base < seg.end; base += 64) {
             const int cnt = seg.end - base < 64 ? seg.end - base : 64;
             int32_t idx_next = a.n;
-            if (base + 64 < seg.end && lane < seg.end - base - 64)
+            float wgt_next = 0.0f;
+            if (base + 64 < seg.end && lane < seg.end - base - 64) {
                 idx_next = __builtin_nontemporal_load(a.sched.zcol + base + 64 + lane);
+                if constexpr (WEIGHTED) wgt_next = __builtin_nontemporal_load(a.sched.zval + base + 64 + lane);
+            }
             int t = 0;
             for (; t + U * NB <= cnt; t += U * NB) {   // full batches; lanes past the end hold the zero row
                 uint4 q[U];
+                float wq[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u) {
                     q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
+                    if constexpr (WEIGHTED) wq[u] = __shfl(wgt, t + u * NB + g);
+                }
 #pragma unroll
-                for (int u = 0; u < U; ++u) sum.add(q[u]);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (WEIGHTED) sum.add_scaled(q[u], wq[u]);
+                    else sum.add(q[u]);
+                }
             }
             if (t < cnt) {
                 const int live = (cnt - t + NB - 1) / NB;
                 uint4 q[U];
+                float wq[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (u < live) q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
-                sum.template add_batch<U>(q, live);
+                    if (u < live) {
+                        q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
+                        if constexpr (WEIGHTED) wq[u] = __shfl(wgt, t + u * NB + g);
+                    }
+                if constexpr (WEIGHTED) sum.template add_batch_scaled<U>(q, wq, live);
+                else sum.template add_batch<U>(q, live);
             }
             idx = idx_next;
+            wgt = wgt_next;
         }
         float tot[V];
         sum.template total<LOG_G>(tot);
@@ -276,10 +313,10 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
 // moves; groups whose row has ended gather the zero row.  `beg`, `len`, `zrow`, `node`, `s` are
 // per-lane values, equal within a lane group; len < 0 for a group without a row (an empty row,
 // len = 0, still gets its all-zero result stored).
-template <typename T, int LOG_G, bool NARROW>
+template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
 __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int32_t beg, const int32_t len,
                                                const int32_t zrow, const int32_t node, const float s,
-                                               const int32_t idx_first, const int lane) {
+                                               const int32_t idx_first, const float wgt_first, const int lane) {
     constexpr int G = 1 << LOG_G;
     constexpr int V = T::kVec;
     constexpr int U = kInFlight < G ? kInFlight : G;
@@ -302,19 +339,30 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
         Sum<T> sum;
         sum.clear();
         int32_t idx = idx_first;
+        float wgt = wgt_first;
         for (int base = 0; base < maxlen; base += G) {
             int32_t idx_next = a.n;
-            if (base + G + c < len) idx_next = __builtin_nontemporal_load(a.sched.zcol + beg + base + G + c);
+            float wgt_next = 0.0f;
+            if (base + G + c < len) {
+                idx_next = __builtin_nontemporal_load(a.sched.zcol + beg + base + G + c);
+                if constexpr (WEIGHTED) wgt_next = __builtin_nontemporal_load(a.sched.zval + beg + base + G + c);
+            }
             const int steps = maxlen - base < G ? maxlen - base : G;
             for (int t = 0; t < steps; t += U) {
                 const int live = steps - t < U ? steps - t : U;
                 uint4 q[U];
+                float wq[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (u < live) q[u] = gather16<T, NARROW>(a, __shfl(idx, group_base + t + u), row_bytes, lane_off);
-                sum.template add_batch<U>(q, live);
+                    if (u < live) {
+                        q[u] = gather16<T, NARROW>(a, __shfl(idx, group_base + t + u), row_bytes, lane_off);
+                        if constexpr (WEIGHTED) wq[u] = __shfl(wgt, group_base + t + u);
+                    }
+                if constexpr (WEIGHTED) sum.template add_batch_scaled<U>(q, wq, live);
+                else sum.template add_batch<U>(q, live);
             }
             idx = idx_next;
+            wgt = wgt_next;
         }
         if (active && len >= 0) finish_vec<T>(a, zrow, node, s, cc * V, sum.acc);
     }
@@ -342,7 +390,7 @@ constexpr int kSingleBlocksPerXcd = 512;
 // workgroups beyond the real ones, all at the end of each XCD's sequence, leave at once.
 // (Measured: spreading the L2-bound A-workgroups evenly among the HBM-bound others, so that both
 // resources are busy all the time, was slower than running them one after the other.)
-template <typename T, int LOG_G, bool NARROW>
+template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
 __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
@@ -362,7 +410,7 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     if (j < n_a) {
 #pragma unroll 1
         for (int64_t t = a_lo + j * kWaves + wave; t < a_hi; t += n_a * kWaves)
-            run_segment<T, LOG_G, NARROW>(a, a.sched.segs[t], lane);
+            run_segment<T, LOG_G, NARROW, WEIGHTED>(a, a.sched.segs[t], lane);
         return;
     }
     const int64_t o = j - n_a;                           // position among the B- and C-workgroups
@@ -373,7 +421,7 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
         const int64_t first = lo + ((o * kXcds + x) * kWaves + wave) * per_wave;
         const int64_t last = first + per_wave < hi ? first + per_wave : hi;
 #pragma unroll 1
-        for (int64_t t = first; t < last; ++t) run_segment<T, LOG_G, NARROW>(a, a.sched.segs[t], lane);
+        for (int64_t t = first; t < last; ++t) run_segment<T, LOG_G, NARROW, WEIGHTED>(a, a.sched.segs[t], lane);
         return;
     }
     const int64_t rb = (o - n_b) * kXcds + x;
@@ -394,6 +442,9 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     const int g = lane >> LOG_G;
     int32_t beg = __shfl(my_beg, g), len = __shfl(my_len, g);
     int32_t idx_cur = c < len ? __builtin_nontemporal_load(a.sched.zcol + beg + c) : a.n;
+    float wgt_cur = 0.0f;
+    if constexpr (WEIGHTED)
+        if (c < len) wgt_cur = __builtin_nontemporal_load(a.sched.zval + beg + c);
 #pragma unroll 1
     for (int r0 = 0; r0 < n_rows; r0 += NB) {
         const int src = r0 + g;      // the row of this lane's group (lanes >= n_rows hold len -1)
@@ -401,11 +452,15 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
         const int32_t nbeg = __shfl(my_beg, nxt);
         const int32_t nlen = r0 + NB < n_rows ? __shfl(my_len, nxt) : -1;
         const int32_t idx_nxt = c < nlen ? __builtin_nontemporal_load(a.sched.zcol + nbeg + c) : a.n;
-        run_short_rows<T, LOG_G, NARROW>(a, beg, len, __shfl(my_row, src), __shfl(my_node, src), __shfl(my_s, src),
-                                         idx_cur, lane);
+        float wgt_nxt = 0.0f;
+        if constexpr (WEIGHTED)
+            if (c < nlen) wgt_nxt = __builtin_nontemporal_load(a.sched.zval + nbeg + c);
+        run_short_rows<T, LOG_G, NARROW, WEIGHTED>(a, beg, len, __shfl(my_row, src), __shfl(my_node, src),
+                                                   __shfl(my_s, src), idx_cur, wgt_cur, lane);
         beg = nbeg;
         len = nlen;
         idx_cur = idx_nxt;
+        wgt_cur = wgt_nxt;
     }
 }
 
@@ -504,17 +559,17 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
     store_vec<T>(z + zrow * F + col, v);
 }
 
-template <typename T, bool NARROW>
+template <typename T, bool NARROW, bool WEIGHTED>
 void launch_spmm(int log_g, dim3 grid, const LayerArgs<T>& a, hipStream_t stream) {
     const dim3 blk(64 * kWaves);
     switch (log_g) {
-        case 0: spmm_rows<T, 0, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        case 1: spmm_rows<T, 1, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        case 2: spmm_rows<T, 2, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        case 3: spmm_rows<T, 3, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        case 4: spmm_rows<T, 4, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        case 5: spmm_rows<T, 5, NARROW><<<grid, blk, 0, stream>>>(a); break;
-        default: spmm_rows<T, 6, NARROW><<<grid, blk, 0, stream>>>(a); break;
+        case 0: spmm_rows<T, 0, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 1: spmm_rows<T, 1, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 2: spmm_rows<T, 2, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 3: spmm_rows<T, 3, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 4: spmm_rows<T, 4, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 5: spmm_rows<T, 5, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        default: spmm_rows<T, 6, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
     }
 }
 
@@ -535,8 +590,11 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     a.b_blocks = (int32_t)b_blocks;
     const dim3 grid((unsigned)(kXcds * (a_blocks + b_blocks + c_blocks)));
     profile_mark(stream, false);
-    if (narrow) launch_spmm<T, true>(log_g, grid, a, stream);
-    else launch_spmm<T, false>(log_g, grid, a, stream);
+    const bool weighted = a.sched.zval != nullptr;
+    if (narrow && weighted) launch_spmm<T, true, true>(log_g, grid, a, stream);
+    else if (narrow) launch_spmm<T, true, false>(log_g, grid, a, stream);
+    else if (weighted) launch_spmm<T, false, true>(log_g, grid, a, stream);
+    else launch_spmm<T, false, false>(log_g, grid, a, stream);
     profile_mark(stream, true);
     E2EG_LAUNCH_CHECK("spmm_rows");
     if (nnz > kSegLen) {  // otherwise no row has several segments
@@ -597,10 +655,10 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
                    const float* dinv, const void* sched, int32_t F, int32_t K, const void* in,
                    int64_t ld_in, typename T::elem* const* store, const int64_t* ld_store,
                    const typename T::elem* const* add, int64_t ld_add, const PropWs& w,
-                   hipStream_t stream) {
+                   bool weighted, hipStream_t stream) {
     using E = typename T::elem;
     SchedView view;
-    sched_carve(const_cast<void*>(sched), n, nnz, &view);
+    sched_carve(const_cast<void*>(sched), n, nnz, &view, weighted);
     const int chunks = F / T::kVec;
     E* z_cur = static_cast<E*>(w.z[0]);
     E* z_next = static_cast<E*>(w.z[1]);
@@ -707,13 +765,14 @@ extern "C" size_t e2eg_propagate_workspace_bytes(int32_t n, int64_t nnz, int32_t
     return carve_prop(nullptr, n, nnz, dtype, F, K).bytes;
 }
 
-extern "C" int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
-                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
-                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
-                                      const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
-                                      int64_t layer_stride, void* ws, size_t ws_bytes,
-                                      void* stream_) {
-    const char* who = "propagate_fwd";
+namespace {
+// `weighted` says which of the two schedule layouts d_sched holds (the weighted one carries the
+// entries' values, which the kernel then multiplies in).
+int32_t propagate_fwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                           const int32_t* d_col_idx, const float* d_dinv_sqrt, const void* d_sched,
+                           int32_t dtype, int32_t F, int32_t K, const void* d_X0, int64_t ldx, void* d_Xout,
+                           int64_t ldo, int64_t layer_stride, void* ws, size_t ws_bytes, void* stream_) {
+    const char* who = weighted ? "propagate_weighted_fwd" : "propagate_fwd";
     int32_t st = check_common(who, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K);
     if (st != E2EG_OK) return st;
     if (K > kMaxLayers) return fail(E2EG_ERR_INVALID_ARG, "%s: K=%d exceeds %d", who, K, kMaxLayers);
@@ -738,23 +797,22 @@ extern "C" int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_r
             store[l - 1] = layer_stride ? static_cast<float*>(d_Xout) + (int64_t)(l - 1) * layer_stride
                                         : (l == K ? static_cast<float*>(d_Xout) : nullptr);
         return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
-                               lds, nullptr, 0, w, stream);
+                               lds, nullptr, 0, w, weighted, stream);
     }
     uint16_t* store[kMaxLayers];
     for (int l = 1; l <= K; ++l)
         store[l - 1] = layer_stride ? static_cast<uint16_t*>(d_Xout) + (int64_t)(l - 1) * layer_stride
                                     : (l == K ? static_cast<uint16_t*>(d_Xout) : nullptr);
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
-                            lds, nullptr, 0, w, stream);
+                            lds, nullptr, 0, w, weighted, stream);
 }
 
-extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
-                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
-                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
-                                      const void* d_gXK, int64_t ldg, const void* d_gLayers,
-                                      int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
-                                      size_t ws_bytes, void* stream_) {
-    const char* who = "propagate_bwd";
+int32_t propagate_bwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                           const int32_t* d_col_idx, const float* d_dinv_sqrt, const void* d_sched,
+                           int32_t dtype, int32_t F, int32_t K, const void* d_gXK, int64_t ldg,
+                           const void* d_gLayers, int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                           size_t ws_bytes, void* stream_) {
+    const char* who = weighted ? "propagate_weighted_bwd" : "propagate_bwd";
     int32_t st = check_common(who, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K);
     if (st != E2EG_OK) return st;
     if (K > kMaxLayers) return fail(E2EG_ERR_INVALID_ARG, "%s: K=%d exceeds %d", who, K, kMaxLayers);
@@ -789,7 +847,7 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
                                                  : nullptr;
         }
         return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
-                               lds, add, ldg, w, stream);
+                               lds, add, ldg, w, weighted, stream);
     }
     uint16_t* store[kMaxLayers];
     const uint16_t* add[kMaxLayers];
@@ -801,7 +859,46 @@ extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_r
                                              : nullptr;
     }
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
-                            lds, add, ldg, w, stream);
+                            lds, add, ldg, w, weighted, stream);
+}
+}  // namespace
+
+extern "C" int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                      const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
+                                      int64_t layer_stride, void* ws, size_t ws_bytes, void* stream) {
+    return propagate_fwd_impl(false, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_X0, ldx,
+                              d_Xout, ldo, layer_stride, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_propagate_weighted_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                               const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                               const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                               const void* d_X0, int64_t ldx, void* d_Xout, int64_t ldo,
+                                               int64_t layer_stride, void* ws, size_t ws_bytes, void* stream) {
+    return propagate_fwd_impl(true, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_X0, ldx,
+                              d_Xout, ldo, layer_stride, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                      const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                      const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                      const void* d_gXK, int64_t ldg, const void* d_gLayers,
+                                      int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                                      size_t ws_bytes, void* stream) {
+    return propagate_bwd_impl(false, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_gXK, ldg,
+                              d_gLayers, g_layer_stride, d_gX0, ldo, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                                               const int32_t* d_col_idx, const float* d_dinv_sqrt,
+                                               const void* d_sched, int32_t dtype, int32_t F, int32_t K,
+                                               const void* d_gXK, int64_t ldg, const void* d_gLayers,
+                                               int64_t g_layer_stride, void* d_gX0, int64_t ldo, void* ws,
+                                               size_t ws_bytes, void* stream) {
+    return propagate_bwd_impl(true, n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, dtype, F, K, d_gXK, ldg,
+                              d_gLayers, g_layer_stride, d_gX0, ldo, ws, ws_bytes, stream);
 }
 
 extern "C" size_t e2eg_aggregate_workspace_bytes(int32_t n, int64_t nnz, int32_t dtype, int32_t F) {

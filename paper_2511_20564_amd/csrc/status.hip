@@ -49,7 +49,7 @@ int32_t fail(int32_t status, const char* fmt, ...) {
     return status;
 }
 
-size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view) {
+size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view, bool weighted) {
     Carver c(base);
     SchedView v;
     v.max_plain = sched_max_plain(nnz);
@@ -66,6 +66,7 @@ size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view) {
     v.slot_base = c.take<int32_t>(v.max_multi);
     v.slot_cnt = c.take<int32_t>(v.max_multi);
     v.segs = c.take<Segment>(v.max_seg);
+    v.zval = weighted ? c.take<float>(nnz > 0 ? nnz : 1) : nullptr;  // last: the rest of the layout is shared
     if (view) *view = v;
     return c.size();
 }

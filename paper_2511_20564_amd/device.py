@@ -44,6 +44,8 @@ class Graph:
     deg: torch.Tensor          # int32 [n]
     dinv_sqrt: torch.Tensor    # float32 [n]
     sched: torch.Tensor        # uint8, opaque
+    val: torch.Tensor | None = None    # float32 [nnz]: entry values of a weighted graph
+    deg_w: torch.Tensor | None = None  # float32 [n]: d~ of a weighted graph (then `deg` is the row length)
 
 
 def normalize(n: int, nnz: int, row_ptr: torch.Tensor, col_idx: torch.Tensor):
@@ -79,6 +81,45 @@ def build_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Te
     return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched)
 
 
+def normalize_weighted(n: int, nnz: int, row_ptr: torch.Tensor, col_idx: torch.Tensor, val: torch.Tensor):
+    """e2eg_normalize_weighted on an existing CSR with values -> (deg_w, dinv_sqrt, sched)."""
+    _require_gpu()
+    assert val.dtype == torch.float32 and val.is_contiguous() and val.numel() >= nnz
+    dev = row_ptr.device
+    deg_w = torch.empty(n, dtype=torch.float32, device=dev)
+    dinv = torch.empty(n, dtype=torch.float32, device=dev)
+    sched = _bytes(B.e2eg_sched_weighted_bytes(n, nnz), dev)
+    ws = _bytes(B.e2eg_normalize_workspace_bytes(n, nnz), dev)
+    B.e2eg_normalize_weighted(n, nnz, row_ptr, col_idx, val, deg_w, dinv, sched, None, ws, None, _stream())
+    return deg_w, dinv, sched
+
+
+def build_weighted_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Tensor,
+                         weights: torch.Tensor) -> Graph:
+    """e2eg_build_csr (with self-loops), e2eg_edge_weights, e2eg_normalize_weighted."""
+    _require_gpu()
+    assert users.dtype == torch.int32 and items.dtype == torch.int32 and weights.dtype == torch.float32
+    assert users.is_cuda and items.is_cuda and weights.is_cuda
+    assert users.is_contiguous() and items.is_contiguous() and weights.is_contiguous()
+    assert users.numel() == items.numel() == weights.numel()
+    dev = users.device
+    n = n_users + n_items
+    n_edges = users.numel()
+    cap = 2 * n_edges + n
+    row_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    ws = _bytes(B.e2eg_build_csr_workspace_bytes(n_users, n_items, n_edges), dev)
+    nnz = B.e2eg_build_csr(n_users, n_items, n_edges, users, items, B.E2EG_ADD_SELF_LOOPS, row_ptr, col, cap, ws,
+                           None, _stream())
+    del ws
+    col_idx = col[:nnz]
+    val = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)[:nnz]
+    B.e2eg_edge_weights(n_users, n_items, n_edges, users, items, weights, nnz, row_ptr, col_idx, val, _stream())
+    deg_w, dinv, sched = normalize_weighted(n, nnz, row_ptr, col_idx, val)
+    deg = (row_ptr[1:] - row_ptr[:-1]).to(torch.int32)
+    return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched, val, deg_w)
+
+
 def propagate_workspace(g: Graph, dtype: torch.dtype, F: int, K: int) -> torch.Tensor:
     code = B.E2EG_F32 if dtype == torch.float32 else B.E2EG_BF16
     return _bytes(B.e2eg_propagate_workspace_bytes(g.n, g.nnz, code, F, K), g.row_ptr.device)
@@ -94,8 +135,9 @@ def propagate_fwd(g: Graph, X0: torch.Tensor, K: int, all_layers: bool = False, 
         out = torch.empty((K, n, F) if all_layers else (n, F), dtype=X0.dtype, device=X0.device)
     if ws is None:
         ws = propagate_workspace(g, X0.dtype, F, K)
-    B.e2eg_propagate_fwd(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(X0), F, K,
-                         X0, X0.stride(0), out, F, n * F if all_layers else 0, ws, None, _stream())
+    fn = B.e2eg_propagate_fwd if g.val is None else B.e2eg_propagate_weighted_fwd
+    fn(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(X0), F, K,
+       X0, X0.stride(0), out, F, n * F if all_layers else 0, ws, None, _stream())
     return out
 
 
@@ -118,8 +160,9 @@ def propagate_bwd(g: Graph, gXK: torch.Tensor, K: int, g_layers: torch.Tensor | 
     if g_shared is not None:
         assert g_layers is None and g_shared.shape == (n, F) and g_shared.is_contiguous() and gXK.stride(0) == F
         g_layers = g_shared
-    B.e2eg_propagate_bwd(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(gXK), F, K,
-                         gXK, gXK.stride(0), g_layers, stride, out, F, ws, None, _stream())
+    fn = B.e2eg_propagate_bwd if g.val is None else B.e2eg_propagate_weighted_bwd
+    fn(g.n, g.nnz, g.row_ptr, g.col_idx, g.dinv_sqrt, g.sched, _dtype_code(gXK), F, K,
+       gXK, gXK.stride(0), g_layers, stride, out, F, ws, None, _stream())
     return out
 
 

@@ -214,6 +214,33 @@ def test_gradnorm_step_is_host_arithmetic(B, oracle):
     assert B.e2eg_block_norms_workspace_bytes(10, 8, 2) > 0 and B.e2eg_block_norms_workspace_bytes(10, 8, 9) == 0
 
 
+def test_weighted_graph_argument_errors(B):
+    w = B.e2eg_edge_weights
+    assert status_of(B, w, 5, 5, -1, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, w, 5, 5, 3, FAKE, FAKE, None, 10, FAKE, FAKE, FAKE) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, w, 5, 5, 3, FAKE, FAKE, FAKE, 10, FAKE, FAKE, None) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, w, 5, 5, 3, FAKE, FAKE, FAKE, 1 << 31, FAKE, FAKE, FAKE) == B.E2EG_ERR_OVERFLOW
+    assert status_of(B, w, 0, 0, 0, None, None, None, 4, FAKE, FAKE, FAKE) == B.E2EG_ERR_INVALID_ARG
+    w(5, 5, 0, None, None, None, 0, FAKE, None, None)            # nothing stored: nothing to do
+    # the weighted schedule is the unweighted one plus the values
+    assert B.e2eg_sched_weighted_bytes(100, 1000) >= B.e2eg_sched_bytes(100, 1000) + 4 * 1000
+    assert B.e2eg_sched_weighted_bytes(-1, 0) == 0
+    nw = B.e2eg_normalize_weighted
+    big = 1 << 30
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, None, None, FAKE, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, None, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, FAKE, FAKE, B.e2eg_sched_bytes(10, 30), FAKE, big) == B.E2EG_ERR_CAPACITY
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, FAKE, FAKE, big, FAKE, 16) == B.E2EG_ERR_WORKSPACE
+    f = B.e2eg_propagate_weighted_fwd
+    assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 6, 2, FAKE, 8, FAKE, 8, 0, FAKE, big) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, None, B.E2EG_F32, 8, 2, FAKE, 8, FAKE, 8, 0, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 8, 2, FAKE, 8, FAKE, 8, 0, FAKE, 16) == B.E2EG_ERR_WORKSPACE
+    f = B.e2eg_propagate_weighted_bwd
+    assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 6, 2, FAKE, 8, None, 0, FAKE, 8, FAKE, big) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 8, 2, None, 8, None, 0, FAKE, 8, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert "propagate_weighted_bwd" in B.e2eg_last_error()
+
+
 def test_profile_aid_rejects_bad_arguments(B):
     assert status_of(B, B.e2eg_profile_begin, -1) == B.E2EG_ERR_INVALID_ARG
     assert status_of(B, B.e2eg_profile_copy, None, None, 16) == B.E2EG_ERR_NULL_PTR

@@ -9,6 +9,7 @@ from .graphs import (  # noqa: F401
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     make_config,
+    make_edge_weights,
     make_features,
     powerlaw_bipartite,
     sample_subgraph,

@@ -60,6 +60,14 @@ def make_features(n: int, F: int, std: float, seed: int, dtype: str) -> np.ndarr
     raise ValueError(dtype)
 
 
+def make_edge_weights(n_edges: int, seed: int) -> np.ndarray:
+    """Interaction strengths for a weighted graph: float32, log-normal around 1 (a few repeat
+    visits are common, heavy engagement is rare), clipped to [0.05, 50]."""
+    rng = np.random.default_rng(seed)
+    w = np.exp(rng.standard_normal(n_edges, dtype=np.float32) * np.float32(0.8))
+    return np.clip(w, np.float32(0.05), np.float32(50.0)).astype(np.float32)
+
+
 # --------------------------------------------------------------------------
 # edge lists
 # --------------------------------------------------------------------------
