@@ -171,6 +171,17 @@ def main():
     gfae["one_stacked_backward_pass_ms"] = round(one_ms, 4)
     del g2, ws2, out2
 
+    # the same step on the weighted graph (A_ij = edge strength): one more float per stored entry
+    from workloads import make_edge_weights
+    uw, iw = torch.from_numpy(c["users"]).cuda(), torch.from_numpy(c["items"]).cuda()
+    ww = torch.from_numpy(make_edge_weights(c["n_edges"], seed=c["seed"] + 4000)).cuda()
+    gw = dev.build_weighted_graph(c["n_users"], c["n_items"], uw, iw, ww)
+    del uw, iw, ww
+    w_ms = event_ms(lambda: (dev.propagate_fwd(gw, X0, K, out=out_f, ws=ws), dev.propagate_bwd(gw, gY, K, out=out_b, ws=ws)), reps=3)
+    weighted = {"ms_per_step": round(w_ms, 4), "GTEPS": round(nnz * K * 2 / (w_ms * 1e-3) / 1e9, 2),
+                "unweighted_ms_per_step": round(ms_per_step, 4)}
+    del gw
+
     # the dense per-layer update on the matrix cores at the mini-batch shape (about 200 k sampled
     # nodes, 128 x 128 weights): forward, and backward (dP and dW); flops and bytes are algorithmic
     nt, Ft = 200_000, 128
@@ -272,7 +283,7 @@ def main():
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
         "build_csr_ms": round(build_ms - normalize_ms, 3), "normalize_ms": round(normalize_ms, 3),
         "alg_GBs": round(alg_bytes * 2 * K / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae, "layer_transform": transform, "launch_bound_case": small,
+        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae, "weighted_edges": weighted, "layer_transform": transform, "launch_bound_case": small,
     }
     print(json.dumps(line), flush=True)
 

@@ -26,6 +26,9 @@ _lib = None
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _i64p = ctypes.POINTER(ctypes.c_int64)
 _f64p = ctypes.POINTER(ctypes.c_double)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_u64p = ctypes.POINTER(ctypes.c_uint64)
 
 
 def build(force: bool = False) -> str:
@@ -57,6 +60,13 @@ def _load():
         lib.e2eg_oracle_edge_values.argtypes = [ctypes.c_int32, ctypes.c_int64, _i32p, _i32p, _f64p, ctypes.c_int64,
                                                 _i64p, _i32p, _f64p]
         lib.e2eg_oracle_weighted_degrees.argtypes = [ctypes.c_int64, _i64p, _f64p, _f64p]
+        lib.e2eg_oracle_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+        lib.e2eg_oracle_sampling_weights.argtypes = [ctypes.c_int64, _f64p, ctypes.c_double, _f64p]
+        lib.e2eg_oracle_sampling_table.argtypes = [ctypes.c_int64, _i64p, _i32p, _f32p, _u64p]
+        lib.e2eg_oracle_sample_subgraph.restype = ctypes.c_int64
+        lib.e2eg_oracle_sample_subgraph.argtypes = [ctypes.c_int64, _i64p, _i32p, _u64p, ctypes.c_int64, _i32p,
+                                                    ctypes.c_int32, _i32p, ctypes.c_uint64, _i32p, _i32p, _i32p,
+                                                    _i64p, ctypes.c_int64]
         lib.e2eg_oracle_propagate_layer_weighted.argtypes = [ctypes.c_int64, _i64p, _i32p, _f64p, _f64p, ctypes.c_int64,
                                                              _f64p, _f64p]
         lib.e2eg_oracle_propagate_layer_weighted_transposed.argtypes = lib.e2eg_oracle_propagate_layer_weighted.argtypes
@@ -356,3 +366,65 @@ def propagate_weighted(row_ptr, col_idx, val, X0, K, transposed=False):
     for _ in range(K):
         H = propagate_layer_weighted(row_ptr, col_idx, val, H, transposed)
     return H
+
+
+# ------------------------------------------------------------------ importance sampling (Section 4.1)
+def philox4x32_10(counter, key):
+    """One block of Philox4x32-10: counter (4 words), key (2 words) -> 4 words."""
+    c, k = _c(counter, np.uint32), _c(key, np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().e2eg_oracle_philox4x32_10(_p(c, _u32p), _p(k, _u32p), _p(out, _u32p))
+    return out
+
+
+def sampling_weights(val, beta):
+    """w^beta per stored entry, the numerator of the sampling probability; 0 where w is not > 0."""
+    val = _c(val, np.float64)
+    p = np.empty_like(val)
+    _load().e2eg_oracle_sampling_weights(val.size, _p(val, _f64p), float(beta), _p(p, _f64p))
+    return p
+
+
+def sampling_table(row_ptr, col_idx, p):
+    """Integer weights q (uint64 [nnz]) of every row's sampling distribution; `p` is taken in float32,
+    the precision in which the scaling to integers is decided."""
+    row_ptr, col_idx, p = _c(row_ptr, np.int64), _c(col_idx, np.int32), _c(p, np.float32)
+    q = np.empty(col_idx.size, dtype=np.uint64)
+    _load().e2eg_oracle_sampling_table(row_ptr.size - 1, _p(row_ptr, _i64p), _p(col_idx, _i32p), _p(p, _f32p),
+                                       _p(q, _u64p))
+    return q
+
+
+def sample_picks(row_ptr, col_idx, q, seeds, fanout, seed):
+    """-> (hop_of [n], src, dst, entry): every pick of the multi-hop sampler in its defined order."""
+    row_ptr, col_idx, q = _c(row_ptr, np.int64), _c(col_idx, np.int32), _c(q, np.uint64)
+    seeds, fanout = _c(seeds, np.int32), _c(fanout, np.int32)
+    n = row_ptr.size - 1
+    cap, width = 0, seeds.size
+    for k in fanout:
+        width = min(width * int(k), n * int(k))
+        cap += width
+    hop_of = np.empty(n, dtype=np.int32)
+    src, dst = np.empty(cap, dtype=np.int32), np.empty(cap, dtype=np.int32)
+    entry = np.empty(cap, dtype=np.int64)
+    m = _load().e2eg_oracle_sample_subgraph(n, _p(row_ptr, _i64p), _p(col_idx, _i32p), _p(q, _u64p), seeds.size,
+                                            _p(seeds, _i32p), fanout.size, _p(fanout, _i32p), int(seed),
+                                            _p(hop_of, _i32p), _p(src, _i32p), _p(dst, _i32p), _p(entry, _i64p), cap)
+    assert m <= cap
+    return hop_of, src[:m].copy(), dst[:m].copy(), entry[:m].copy()
+
+
+def sample_subgraph(n_users, row_ptr, col_idx, q, seeds, fanout, seed):
+    """The sampled subgraph in local numbering: nodes of the subgraph in ascending global id (users
+    come first because they do in the parent), every pick as a (local user, local item) pair in pick
+    order, and the index of the parent's stored entry it came from.
+    -> dict(nodes, n_users, n_items, users, items, entry, hop_of)"""
+    hop_of, src, dst, entry = sample_picks(row_ptr, col_idx, q, seeds, fanout, seed)
+    nodes = np.nonzero(hop_of)[0].astype(np.int32)
+    nu = int(np.searchsorted(nodes, n_users))
+    user_end = np.where(src < n_users, src, dst)      # an edge joins a user and an item
+    item_end = np.where(src < n_users, dst, src)
+    assert (user_end < n_users).all() and (item_end >= n_users).all()
+    return dict(nodes=nodes, n_users=nu, n_items=int(nodes.size - nu),
+                users=np.searchsorted(nodes, user_end).astype(np.int32),
+                items=(np.searchsorted(nodes, item_end) - nu).astype(np.int32), entry=entry, hop_of=hop_of)

@@ -35,6 +35,14 @@
  *   - GradNorm task weighting (Section 4.3.1): G_i = || grad_{h(0)} (w_i L_i) ||_2, relative rates
  *     r_i = (L_i / L_i(0)) / mean_j (L_j / L_j(0)), meta-loss sum_i | G_i - Gbar r_i^gamma |, one
  *     gradient step on the weights and renormalisation to sum_i w_i = T.
+ *   - Importance sampling of a multi-hop subgraph (Section 4.1, the sampling probability
+ *     p(u->v) = w_uv^beta / sum_k w_uk^beta, at most k neighbours per node, depth L; Section 5,
+ *     "Subgraph Sampling": fan-outs per hop).  A node with at most k stored neighbours keeps all that
+ *     have positive weight; otherwise k independent draws are made from the distribution and equal
+ *     draws are one neighbour.  The distribution is held in integers (weights scaled to 2^24 at the
+ *     row maximum) and the random numbers come from the counter-based generator Philox4x32-10
+ *     (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC 2011), so that
+ *     every decision is integer arithmetic.
  *   - Dense per-layer update Z = P W, H' = max(Z, 0): the update function psi of
  *     the generic message-passing layer with the W, sigma of the GraphSAGE
  *     layer (Section 3 and Section 3.1), and its backward.
@@ -390,4 +398,108 @@ void e2eg_oracle_propagate_layer_weighted_transposed(int64_t n, const int64_t* r
             for (int64_t f = 0; f < F; ++f) o[f] += a * g[f];
         }
     }
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Importance sampling (Section 4.1).
+ * ------------------------------------------------------------------------------------------- */
+
+/* Philox4x32-10 as published (SC 2011): ten rounds; a round multiplies words 0 and 2 of the counter
+ * by two fixed odd constants, the high halves are mixed with the other two words and the key, the
+ * low halves pass through; the key grows by two Weyl constants after every round. */
+void e2eg_oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 64 random bits of draw t of node u at hop h under a 64-bit seed: counter (t, u, h, 0), key =
+ * the two halves of the seed, words 0 (low) and 1 (high) of the output. */
+static uint64_t draw_bits(uint64_t seed, uint32_t hop, uint32_t node, uint32_t t) {
+    uint32_t ctr[4] = {t, node, hop, 0u}, key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)}, out[4];
+    e2eg_oracle_philox4x32_10(ctr, key, out);
+    return (uint64_t)out[0] | ((uint64_t)out[1] << 32);
+}
+
+/* w^beta for every stored entry (the numerator of the sampling probability). */
+void e2eg_oracle_sampling_weights(int64_t nnz, const double* val, double beta, double* p) {
+    for (int64_t e = 0; e < nnz; ++e) p[e] = val[e] > 0.0 ? pow(val[e], beta) : 0.0;
+}
+
+/* Integer form of one row's distribution, decided in single precision: q_e = floor(p_e / pmax * 2^24),
+ * at least 1 where p_e > 0; the diagonal entry, entries that are not positive and entries that are
+ * not finite get 0 (a node is not its own neighbour), and pmax is the largest usable p of the row. */
+void e2eg_oracle_sampling_table(int64_t n, const int64_t* row_ptr, const int32_t* col_idx, const float* p,
+                                uint64_t* q) {
+    for (int64_t i = 0; i < n; ++i) {
+        float pmax = 0.0f;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e)
+            if (col_idx[e] != i && p[e] > 0.0f && p[e] <= 3.402823466e38f && p[e] > pmax) pmax = p[e];
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            q[e] = 0;
+            if (col_idx[e] != i && p[e] > 0.0f && p[e] <= 3.402823466e38f) {
+                float scaled = floorf(p[e] / pmax * 16777216.0f);
+                q[e] = scaled >= 1.0f ? (uint64_t)scaled : 1u;
+            }
+        }
+    }
+}
+
+/*
+ * Multi-hop sampling from `n_seeds` seed nodes with fan-out fanout[h] at hop h = 0..L-1.
+ * hop_of[v] (output, [n]) = 0 if v is not in the subgraph, 1 for a seed, h + 2 for a node first
+ * reached at hop h.  The frontier of hop 0 is the set of seeds, that of hop h + 1 the nodes first
+ * reached at hop h; a frontier is walked in ascending node order, the draws of a node in order of
+ * their index.  Every pick is written as (source node, picked neighbour, index of the stored entry);
+ * returns the number of picks (never more than `cap` are written).
+ */
+int64_t e2eg_oracle_sample_subgraph(int64_t n, const int64_t* row_ptr, const int32_t* col_idx, const uint64_t* q,
+                                    int64_t n_seeds, const int32_t* seeds, int32_t L, const int32_t* fanout,
+                                    uint64_t seed, int32_t* hop_of, int32_t* src, int32_t* dst, int64_t* entry,
+                                    int64_t cap) {
+    int64_t picks = 0;
+    for (int64_t v = 0; v < n; ++v) hop_of[v] = 0;
+    for (int64_t s = 0; s < n_seeds; ++s) hop_of[seeds[s]] = 1;
+    for (int32_t h = 0; h < L; ++h) {
+        const int64_t k = fanout[h];
+        for (int64_t u = 0; u < n; ++u) {
+            if (hop_of[u] != h + 1) continue;
+            const int64_t beg = row_ptr[u], end = row_ptr[u + 1];
+            for (int64_t t = 0; t < k; ++t) {
+                int64_t e = -1;
+                if (end - beg <= k) {           /* few neighbours: all that can be drawn at all */
+                    if (t < end - beg && q[beg + t] > 0) e = beg + t;
+                } else {
+                    uint64_t total = 0;
+                    for (int64_t x = beg; x < end; ++x) total += q[x];
+                    if (total > 0) {
+                        /* r uniform on [0, total): the high half of the 128-bit product bits * total */
+                        uint64_t r = (uint64_t)(((unsigned __int128)draw_bits(seed, (uint32_t)h, (uint32_t)u, (uint32_t)t) * total) >> 64);
+                        uint64_t acc = 0;
+                        for (int64_t x = beg; x < end; ++x) {
+                            acc += q[x];
+                            if (acc > r) { e = x; break; }
+                        }
+                    }
+                }
+                if (e < 0) continue;
+                const int32_t v = col_idx[e];
+                if (hop_of[v] == 0) hop_of[v] = h + 2;
+                if (picks < cap) { src[picks] = (int32_t)u; dst[picks] = v; entry[picks] = e; }
+                ++picks;
+            }
+        }
+    }
+    return picks;
 }

@@ -705,3 +705,153 @@ def test_weighted_single_edge_closed_form_and_unit_weights(oracle):
     val = oracle.edge_values(nu, u, i, np.ones(u.size), row_ptr, col)
     X = np.random.default_rng(2).standard_normal((nu + ni, 3))
     assert relerr(oracle.propagate_layer_weighted(row_ptr, col, val, X), oracle.propagate_layer(row_ptr, col, X)) < 1e-14
+
+
+# ---------------------------------------------------------------- importance sampling (Section 4.1)
+def test_philox_known_answers(oracle):
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        rows = [[int(w, 16) for w in line.split()] for line in f if line.strip() and not line.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        assert list(oracle.philox4x32_10(r[0:4], r[4:6])) == r[6:10]
+
+
+def one_user_graph(oracle, weights):
+    """User 0 joined to items 0..m-1 with the given weights; -> (row_ptr, col, val)."""
+    m = len(weights)
+    u, i = np.zeros(m, np.int32), np.arange(m, dtype=np.int32)
+    row_ptr, col = oracle.build_csr(1, m, u, i)
+    return row_ptr, col, oracle.edge_values(1, u, i, np.asarray(weights, np.float64), row_ptr, col)
+
+
+def test_sampling_weights_are_powers(oracle):
+    w = np.array([0.5, 2.0, 0.0, 3.0, -1.0, 7.25])
+    assert np.array_equal(oracle.sampling_weights(w, 1.0), np.where(w > 0, w, 0.0))
+    assert np.array_equal(oracle.sampling_weights(w, 0.0), (w > 0).astype(np.float64))    # beta = 0: uniform
+    assert np.allclose(oracle.sampling_weights(w, 2.5), np.where(w > 0, np.abs(w) ** 2.5, 0.0), rtol=1e-15)
+
+
+def test_sampling_table_is_the_distribution_in_integers(oracle):
+    rng = np.random.default_rng(4)
+    nu, ni, u, i = small_graph(21, nu=30, ni=20, ne=300)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    p = rng.uniform(0.01, 5.0, size=col.size).astype(np.float32)
+    bad = rng.choice(col.size, size=40, replace=False)
+    p[bad[:10]], p[bad[10:20]], p[bad[20:30]], p[bad[30:]] = 0.0, -1.0, np.nan, np.inf
+    q = oracle.sampling_table(row_ptr, col, p)
+    for r in range(nu + ni):
+        sl = slice(row_ptr[r], row_ptr[r + 1])
+        ok = (col[sl] != r) & (p[sl] > 0) & np.isfinite(p[sl])
+        assert np.array_equal(q[sl] > 0, ok)                 # the diagonal and unusable entries cannot be drawn
+        if ok.any():
+            assert q[sl].max() == 1 << 24                    # the largest weight of the row maps to 2^24
+            pr = p[sl][ok].astype(np.float64)
+            assert np.allclose(q[sl][ok] / q[sl][ok].sum(), pr / pr.sum(), rtol=2e-5)
+    # a weight far below the row maximum keeps the smallest positive chance instead of none
+    row_ptr, col, _ = one_user_graph(oracle, [1.0, 1.0])
+    q = oracle.sampling_table(row_ptr, col, np.array([0.0, 1.0, 1e-12, 1.0, 1.0], np.float32)[:col.size])
+    assert sorted(q[row_ptr[0]:row_ptr[1]].tolist()) == [0, 1, 1 << 24]
+
+
+def test_sampler_pick_follows_from_the_random_bits(oracle):
+    """Three neighbours with integer weights 2^24, 2^23, 2^23 (total 2^25): the pick of draw t is
+    decided by r = floor(bits * total / 2^64), worked out here with Python integers from the
+    generator's output for counter (t, node, hop, 0) and the seed's halves as key."""
+    row_ptr, col, val = one_user_graph(oracle, [2.0, 1.0, 1.0])
+    q = oracle.sampling_table(row_ptr, col, val.astype(np.float32))
+    assert q[row_ptr[0]:row_ptr[1]].tolist() == [0, 1 << 24, 1 << 23, 1 << 23]
+    seed = 0x1234567890ABCDEF
+    hop_of, src, dst, entry = oracle.sample_picks(row_ptr, col, q, [0], [2], seed)
+    assert src.tolist() == [0, 0] and hop_of[0] == 1
+    for t in range(2):
+        out = oracle.philox4x32_10([t, 0, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        r = ((int(out[0]) | (int(out[1]) << 32)) * (1 << 25)) >> 64
+        want = 1 if r < (1 << 24) else 2 if r < (1 << 24) + (1 << 23) else 3
+        assert dst[t] == want and entry[t] == row_ptr[0] + want
+    # second hop, from item node 2 (a row of two entries: user 0 and itself) with fan-out 1 < 2 entries
+    hop_of, src, dst, entry = oracle.sample_picks(row_ptr, col, q, [2], [1, 2], seed)
+    assert src.tolist()[0] == 2 and dst.tolist()[0] == 0 and hop_of[0] == 2   # its only neighbour, whatever the bits
+    for t in range(2):                                                         # hop 1 from node 0: counter (t, 0, 1, 0)
+        out = oracle.philox4x32_10([t, 0, 1, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        r = ((int(out[0]) | (int(out[1]) << 32)) * (1 << 25)) >> 64
+        want = 1 if r < (1 << 24) else 2 if r < (1 << 24) + (1 << 23) else 3
+        assert src[1 + t] == 0 and dst[1 + t] == want
+
+
+@pytest.mark.parametrize("beta", [0.0, 1.0, 1.7])
+def test_sampler_frequencies_follow_the_sampling_probability(oracle, beta):
+    """Draws of one node over many seeds are independent samples of p(u->v) = w^beta / sum w^beta:
+    a chi-square test of the counts against that distribution (39 degrees of freedom)."""
+    rng = np.random.default_rng(8)
+    w = rng.uniform(0.2, 4.0, size=40)
+    row_ptr, col, val = one_user_graph(oracle, w)
+    q = oracle.sampling_table(row_ptr, col, oracle.sampling_weights(val, beta).astype(np.float32))
+    counts = np.zeros(41)
+    reps, k = 3000, 8
+    for s in range(reps):
+        _, src, dst, _ = oracle.sample_picks(row_ptr, col, q, [0], [k], 1000 + s)
+        assert src.size == k
+        counts += np.bincount(dst, minlength=41)
+    assert counts[0] == 0                                   # never the node itself
+    prob = w ** beta / (w ** beta).sum()
+    chi2 = (((counts[1:] - reps * k * prob) ** 2) / (reps * k * prob)).sum()
+    assert chi2 < 39 + 5 * np.sqrt(2 * 39), chi2
+    # and a planted mistake (the neighbour after the drawn one) is far outside
+    shifted = np.roll(counts[1:], 1)
+    assert (((shifted - reps * k * prob) ** 2) / (reps * k * prob)).sum() > 10 * 39 or beta == 0.0
+
+
+def test_sampler_large_beta_keeps_the_strongest_neighbour(oracle):
+    w = np.array([1.0, 1.5, 0.7, 3.0, 2.9, 0.1, 1.1, 2.0]) / 3.0
+    row_ptr, col, val = one_user_graph(oracle, w)
+    q = oracle.sampling_table(row_ptr, col, oracle.sampling_weights(val, 2000.0).astype(np.float32))
+    assert q[row_ptr[0]:row_ptr[1]].max() == 1 << 24 and np.sort(q[row_ptr[0]:row_ptr[1]])[-2] <= 1
+    _, _, dst, _ = oracle.sample_picks(row_ptr, col, q, [0], [4], 5)
+    assert dst.tolist() == [4, 4, 4, 4]                     # item 3 = node 4; (2.9/3)^2000 is below 2^-24
+
+
+def test_sampler_structure(oracle):
+    """Two hops on a power-law graph: what must hold for any random bits."""
+    c = make_config(2, scale=0.02, features=False)
+    nu, ni = c["n_users"], c["n_items"]
+    n = nu + ni
+    row_ptr, col = oracle.build_csr(nu, ni, c["users"], c["items"])
+    rng = np.random.default_rng(3)
+    w = rng.uniform(0.1, 3.0, size=c["users"].size)
+    w[::9] = 0.0                                            # edges that are stored but cannot be drawn
+    val = oracle.edge_values(nu, c["users"], c["items"], w, row_ptr, col)
+    q = oracle.sampling_table(row_ptr, col, oracle.sampling_weights(val, 1.0).astype(np.float32))
+    seeds = rng.choice(nu, size=50, replace=False).astype(np.int32)
+    seeds = np.concatenate([seeds, seeds[:5]])              # a seed given twice is one seed
+    fan = [6, 4]
+    hop_of, src, dst, entry = oracle.sample_picks(row_ptr, col, q, seeds, fan, 77)
+    row_of_entry = np.searchsorted(row_ptr, entry, side="right") - 1
+    assert np.array_equal(row_of_entry, src) and np.array_equal(col[entry], dst)      # picks are stored entries
+    assert (q[entry] > 0).all() and (src != dst).all()
+    assert set(np.nonzero(hop_of == 1)[0]) == set(seeds.tolist())
+    assert (hop_of[dst] >= 1).all() and (hop_of[dst] <= hop_of[src] + 1).all()
+    deg = np.diff(row_ptr)
+    for h, k in enumerate(fan):
+        frontier = np.nonzero(hop_of == h + 1)[0]
+        sel = hop_of[src] == h + 1
+        per_node = np.bincount(src[sel], minlength=n)
+        assert per_node[np.setdiff1d(np.arange(n), frontier)].sum() == 0              # only the frontier is expanded
+        for u in frontier:
+            mine = np.sort(entry[sel & (src == u)])
+            usable = np.arange(row_ptr[u], row_ptr[u + 1])[q[row_ptr[u]:row_ptr[u + 1]] > 0]
+            if deg[u] <= k:
+                assert np.array_equal(mine, usable)                                    # few neighbours: all of them
+            else:
+                assert mine.size == (k if usable.size else 0)                          # else exactly k draws
+        reached = np.nonzero(hop_of == h + 2)[0]                                       # first reached at this hop
+        assert set(reached.tolist()) <= set(dst[sel].tolist())
+    assert (hop_of[src] <= len(fan)).all()                                             # the last hop's nodes are leaves
+    # local numbering
+    s = oracle.sample_subgraph(nu, row_ptr, col, q, seeds, fan, 77)
+    assert np.array_equal(s["nodes"], np.nonzero(hop_of)[0]) and s["n_users"] == (s["nodes"] < nu).sum()
+    gu, gi = s["nodes"][s["users"]], s["nodes"][s["n_users"] + s["items"]]
+    assert np.array_equal(np.minimum(src, dst), gu) and np.array_equal(np.maximum(src, dst), gi)
+    # another seed gives other picks; the same seed the same
+    again = oracle.sample_picks(row_ptr, col, q, seeds, fan, 77)
+    other = oracle.sample_picks(row_ptr, col, q, seeds, fan, 78)
+    assert np.array_equal(again[3], entry) and not np.array_equal(other[3][:entry.size], entry[:other[3].size])
