@@ -180,7 +180,26 @@ def main():
     w_ms = event_ms(lambda: (dev.propagate_fwd(gw, X0, K, out=out_f, ws=ws), dev.propagate_bwd(gw, gY, K, out=out_b, ws=ws)), reps=3)
     weighted = {"ms_per_step": round(w_ms, 4), "GTEPS": round(nnz * K * 2 / (w_ms * 1e-3) / 1e9, 2),
                 "unweighted_ms_per_step": round(ms_per_step, 4)}
-    del gw
+
+    # importance sampling on that graph (the step before the path): the table once per graph, then one
+    # two-hop subgraph per call for 4096 seed users, fan-outs (25, 10), p ~ w^1.5; wall time per call
+    # (the call waits for its counts)
+    t1 = time.perf_counter()
+    table = dev.sampler_table(gw, beta=1.5)
+    torch.cuda.synchronize()
+    table_ms = (time.perf_counter() - t1) * 1e3
+    seeds_t = torch.from_numpy(np.sort(np.random.default_rng(c["seed"]).choice(c["n_users"], size=4096, replace=False)).astype(np.int32)).cuda()
+    fan = [25, 10]
+    sws = torch.empty(B.e2eg_sample_subgraph_workspace_bytes(n, 4096, fan), dtype=torch.uint8, device="cuda")
+    sub = dev.sample_subgraph(gw, table, seeds_t, fan, 1, ws=sws)
+    t1 = time.perf_counter()
+    for r in range(10):
+        sub = dev.sample_subgraph(gw, table, seeds_t, fan, 2 + r, ws=sws)
+    sample_ms = (time.perf_counter() - t1) / 10 * 1e3
+    sampler = {"table_ms": round(table_ms, 3), "sample_ms": round(sample_ms, 4), "seeds": 4096, "fanout": fan,
+               "picks": int(sub["users"].numel()), "nodes": int(sub["n_users"] + sub["n_items"]),
+               "Mpicks_per_s": round(sub["users"].numel() / sample_ms / 1e3, 2)}
+    del gw, table, sws, sub
 
     # the dense per-layer update on the matrix cores at the mini-batch shape (about 200 k sampled
     # nodes, 128 x 128 weights): forward, and backward (dP and dW); flops and bytes are algorithmic
@@ -283,7 +302,7 @@ def main():
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
         "build_csr_ms": round(build_ms - normalize_ms, 3), "normalize_ms": round(normalize_ms, 3),
         "alg_GBs": round(alg_bytes * 2 * K / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae, "weighted_edges": weighted, "layer_transform": transform, "launch_bound_case": small,
+        "roofline": roofline, "cpu_baseline": cpu, "gfae_branch": gfae, "weighted_edges": weighted, "importance_sampler": sampler, "layer_transform": transform, "launch_bound_case": small,
     }
     print(json.dumps(line), flush=True)
 

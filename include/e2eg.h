@@ -278,6 +278,54 @@ int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row
                                     size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Importance sampling of a multi-hop subgraph (Section 4.1: neighbour v of u is drawn with
+ * probability w_uv^beta / sum_k w_uk^beta, at most k neighbours per node, depth L; Section 5,
+ * "Subgraph Sampling": one fan-out per hop).  The parent graph is a CSR from e2eg_build_csr (users
+ * are nodes [0, n_users), items the rest) with values as for the weighted path.  The result is the
+ * step before the path: local (user, item) pairs ready for e2eg_build_csr.
+ *
+ * e2eg_sampling_weights: d_p[e] = d_val[e]^beta where d_val[e] > 0, else 0 (beta >= 0; beta = 1
+ * copies, beta = 0 gives the uniform sampler).
+ *
+ * e2eg_sampler_prepare: the sampling table of a graph, made once per graph.  Each row's weights d_p
+ * become integers, floor(p / pmax * 2^24) with pmax the row's largest usable weight, decided in fp32
+ * with IEEE rounding, at least 1 where p > 0; the diagonal entry and entries that are not positive
+ * and finite get 0 and are never drawn.  d_table (e2eg_sampler_table_bytes(nnz), 256-byte aligned)
+ * receives their running sums over the whole CSR (nnz + 1 values of 64 bits).
+ *
+ * e2eg_sample_subgraph: hop h = 0..L-1 expands its frontier (hop 0: the distinct seeds; hop h+1:
+ * the nodes first reached at hop h), each frontier node u with fan-out k = h_fanout[h] (HOST array):
+ * a row of at most k stored entries keeps every entry that can be drawn; otherwise k independent
+ * draws are made, draw t taking r = floor(bits * total / 2^64) with bits = words 0 (low) and 1 (high)
+ * of Philox4x32-10 at counter (t, u, h, 0) under key (seed low half, seed high half), and picking the
+ * first entry whose running sum within the row exceeds r.  Equal draws are kept as equal pairs
+ * (e2eg_build_csr counts a repeated pair once).
+ * Outputs: d_nodes = the global ids of the subgraph's nodes in ascending order (local id = position;
+ * users come first); the picks in order (hop, frontier node ascending, draw) as local pairs
+ * d_edge_users / d_edge_items (item ids counted from 0) and, if d_edge_w is not NULL, the value
+ * d_val[entry] of each; h_counts (HOST int32[3]) = local users, local items, pairs.
+ * node_capacity >= min(n, n_seeds + C) and edge_capacity >= C with C = e2eg_sample_capacity(...)
+ * (the number of draws the fan-outs allow), else CAPACITY.  1 <= L <= 8, fan-outs in [1, 65536].
+ * Errors: BAD_INDEX for a seed out of range or a stored entry that joins two users or two items
+ * (outputs then unspecified).  Integer arithmetic only: the result depends on the inputs and the
+ * seed alone.  Waits for the stream once, at the end.
+ */
+int32_t e2eg_sampling_weights(int64_t nnz, const float* d_val, float beta, float* d_p, void* stream);
+size_t e2eg_sampler_table_bytes(int64_t nnz);
+size_t e2eg_sampler_prepare_workspace_bytes(int64_t nnz);
+int32_t e2eg_sampler_prepare(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                             const float* d_p, void* d_table, size_t table_bytes, void* ws, size_t ws_bytes,
+                             void* stream);
+int64_t e2eg_sample_capacity(int32_t n, int32_t n_seeds, int32_t L, const int32_t* h_fanout);
+size_t e2eg_sample_subgraph_workspace_bytes(int32_t n, int32_t n_seeds, int32_t L, const int32_t* h_fanout);
+int32_t e2eg_sample_subgraph(int32_t n_users, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
+                             const int32_t* d_col_idx, const void* d_table, const float* d_val,
+                             int32_t n_seeds, const int32_t* d_seeds, int32_t L, const int32_t* h_fanout,
+                             uint64_t seed, int32_t* d_nodes, int64_t node_capacity, int32_t* d_edge_users,
+                             int32_t* d_edge_items, float* d_edge_w, int64_t edge_capacity, int32_t* h_counts,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement aid (not part of the path): per-launch duration of the neighbour-sum kernel, the
  * kernel that moves nearly all bytes of e2eg_propagate_*.  Between e2eg_profile_begin() and
  * e2eg_profile_end() every launch of that kernel made by the calling thread is bracketed by a

@@ -57,6 +57,15 @@ SIGNATURES = {
     "e2eg_normalize_weighted": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
     "e2eg_propagate_weighted_fwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "e2eg_propagate_weighted_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
+    "e2eg_sampling_weights": (_i32, [_i64, _vp, ctypes.c_float, _vp, _vp]),
+    "e2eg_sampler_table_bytes": (_sz, [_i64]),
+    "e2eg_sampler_prepare_workspace_bytes": (_sz, [_i64]),
+    "e2eg_sampler_prepare": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_sample_capacity": (_i64, [_i32, _i32, _i32, ctypes.POINTER(_i32)]),
+    "e2eg_sample_subgraph_workspace_bytes": (_sz, [_i32, _i32, _i32, ctypes.POINTER(_i32)]),
+    "e2eg_sample_subgraph": (_i32, [_i32, _i32, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _i32, ctypes.POINTER(_i32),
+                                    ctypes.c_uint64, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i32), _vp, _sz,
+                                    _vp]),
     "e2eg_profile_begin": (_i32, [_i32]),
     "e2eg_profile_end": (_i32, [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]),
     "e2eg_profile_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
@@ -201,6 +210,56 @@ def e2eg_propagate_weighted_bwd(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sch
                                                       _ptr(d_sched), dtype, F, K, _ptr(d_gXK), ldg, _ptr(d_gLayers),
                                                       g_layer_stride, _ptr(d_gX0), ldo, _ptr(ws),
                                                       _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_sampling_weights(nnz, d_val, beta, d_p, stream=0):
+    _check(load_library().e2eg_sampling_weights(nnz, _ptr(d_val), beta, _ptr(d_p), stream or None))
+
+
+def e2eg_sampler_table_bytes(nnz) -> int:
+    return int(load_library().e2eg_sampler_table_bytes(nnz))
+
+
+def e2eg_sampler_prepare_workspace_bytes(nnz) -> int:
+    return int(load_library().e2eg_sampler_prepare_workspace_bytes(nnz))
+
+
+def e2eg_sampler_prepare(n, nnz, d_row_ptr, d_col_idx, d_p, d_table, table_bytes, ws, ws_bytes=None, stream=0):
+    _check(load_library().e2eg_sampler_prepare(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_p), _ptr(d_table),
+                                               _nbytes(d_table) if table_bytes is None else table_bytes, _ptr(ws),
+                                               _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def _fanout_array(fanout):
+    return (_i32 * len(fanout))(*[int(k) for k in fanout]) if fanout is not None else None
+
+
+def e2eg_sample_capacity(n, n_seeds, fanout) -> int:
+    """-> the number of draws the fan-outs allow (raises on bad arguments)."""
+    cap = int(load_library().e2eg_sample_capacity(n, n_seeds, len(fanout) if fanout is not None else 0,
+                                                  _fanout_array(fanout)))
+    if cap < 0:
+        raise E2egError(E2EG_ERR_INVALID_ARG, e2eg_last_error())
+    return cap
+
+
+def e2eg_sample_subgraph_workspace_bytes(n, n_seeds, fanout) -> int:
+    return int(load_library().e2eg_sample_subgraph_workspace_bytes(n, n_seeds, len(fanout), _fanout_array(fanout)))
+
+
+def e2eg_sample_subgraph(n_users, n, nnz, d_row_ptr, d_col_idx, d_table, d_val, n_seeds, d_seeds, fanout, seed, d_nodes,
+                         node_capacity, d_edge_users, d_edge_items, d_edge_w, edge_capacity, ws, ws_bytes=None,
+                         stream=0):
+    """-> (local users, local items, pairs)"""
+    counts = (_i32 * 3)()
+    _check(load_library().e2eg_sample_subgraph(n_users, n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_table),
+                                               _ptr(d_val), n_seeds, _ptr(d_seeds),
+                                               len(fanout) if fanout is not None else 0, _fanout_array(fanout),
+                                               ctypes.c_uint64(seed), _ptr(d_nodes), node_capacity,
+                                               _ptr(d_edge_users), _ptr(d_edge_items), _ptr(d_edge_w), edge_capacity,
+                                               counts, _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                               stream or None))
+    return int(counts[0]), int(counts[1]), int(counts[2])
 
 
 def e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype) -> int:

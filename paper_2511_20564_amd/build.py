@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libe2eg.so")
-SOURCES = ["status.hip", "scan.hip", "sort.hip", "build_csr.hip", "normalize.hip", "propagate.hip", "transform.hip", "readout.hip"]
+SOURCES = ["status.hip", "scan.hip", "sort.hip", "build_csr.hip", "normalize.hip", "propagate.hip", "transform.hip", "readout.hip", "sampler.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

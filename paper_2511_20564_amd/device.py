@@ -120,6 +120,45 @@ def build_weighted_graph(n_users: int, n_items: int, users: torch.Tensor, items:
     return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched, val, deg_w)
 
 
+def sampler_table(g: Graph, beta: float = 1.0, p: torch.Tensor | None = None) -> torch.Tensor:
+    """The sampling table of a weighted graph: e2eg_sampling_weights (unless `p`, float32 [nnz], is
+    given) and e2eg_sampler_prepare."""
+    _require_gpu()
+    dev = g.row_ptr.device
+    if p is None:
+        assert g.val is not None
+        p = torch.empty(max(g.nnz, 1), dtype=torch.float32, device=dev)
+        B.e2eg_sampling_weights(g.nnz, g.val, float(beta), p, _stream())
+    assert p.dtype == torch.float32 and p.is_contiguous() and p.numel() >= g.nnz
+    table = _bytes(B.e2eg_sampler_table_bytes(g.nnz), dev)
+    ws = _bytes(B.e2eg_sampler_prepare_workspace_bytes(g.nnz), dev)
+    B.e2eg_sampler_prepare(g.n, g.nnz, g.row_ptr, g.col_idx, p, table, None, ws, None, _stream())
+    return table
+
+
+def sample_subgraph(g: Graph, table: torch.Tensor, seeds: torch.Tensor, fanout, seed: int,
+                    with_weights: bool = True, ws: torch.Tensor | None = None) -> dict:
+    """e2eg_sample_subgraph -> dict(nodes, n_users, n_items, users, items, weights): global ids of the
+    local nodes, and the picks as local (user, item) pairs (with the parent's values)."""
+    _require_gpu()
+    assert seeds.dtype == torch.int32 and seeds.is_cuda and seeds.is_contiguous()
+    dev = g.row_ptr.device
+    n_seeds = seeds.numel()
+    cap = B.e2eg_sample_capacity(g.n, n_seeds, fanout)
+    node_cap = min(g.n, n_seeds + cap)
+    nodes = torch.empty(max(node_cap, 1), dtype=torch.int32, device=dev)
+    eu = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    ei = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    ew = torch.empty(max(cap, 1), dtype=torch.float32, device=dev) if with_weights and g.val is not None else None
+    if ws is None:
+        ws = _bytes(B.e2eg_sample_subgraph_workspace_bytes(g.n, n_seeds, fanout), dev)
+    nu, ni, ne = B.e2eg_sample_subgraph(g.n_users, g.n, g.nnz, g.row_ptr, g.col_idx, table,
+                                        g.val if ew is not None else None, n_seeds, seeds, fanout, seed, nodes,
+                                        node_cap, eu, ei, ew, cap, ws, None, _stream())
+    return dict(nodes=nodes[:nu + ni], n_users=nu, n_items=ni, users=eu[:ne], items=ei[:ne],
+                weights=ew[:ne] if ew is not None else None)
+
+
 def propagate_workspace(g: Graph, dtype: torch.dtype, F: int, K: int) -> torch.Tensor:
     code = B.E2EG_F32 if dtype == torch.float32 else B.E2EG_BF16
     return _bytes(B.e2eg_propagate_workspace_bytes(g.n, g.nnz, code, F, K), g.row_ptr.device)

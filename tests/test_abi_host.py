@@ -241,6 +241,46 @@ def test_weighted_graph_argument_errors(B):
     assert "propagate_weighted_bwd" in B.e2eg_last_error()
 
 
+def test_sampler_argument_errors(B):
+    big = 1 << 30
+    assert status_of(B, B.e2eg_sampling_weights, 10, FAKE, -1.0, FAKE) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_sampling_weights, 10, FAKE, float("nan"), FAKE) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, B.e2eg_sampling_weights, 10, None, 1.0, FAKE) == B.E2EG_ERR_NULL_PTR
+    B.e2eg_sampling_weights(0, None, 1.0, None)
+    assert B.e2eg_sampler_table_bytes(1000) >= 8 * 1001 and B.e2eg_sampler_table_bytes(-1) == 0
+    pr = B.e2eg_sampler_prepare
+    assert status_of(B, pr, 10, 30, FAKE, FAKE, None, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, pr, 10, 30, FAKE, FAKE, FAKE, FAKE, 64, FAKE, big) == B.E2EG_ERR_CAPACITY
+    assert status_of(B, pr, 10, 30, FAKE, FAKE, FAKE, FAKE, big, FAKE, 0) == B.E2EG_ERR_WORKSPACE
+    assert status_of(B, pr, 10, 1 << 31, FAKE, FAKE, FAKE, FAKE, big, FAKE, big) == B.E2EG_ERR_OVERFLOW
+    # the plan: seeds x fan-outs, a frontier never larger than the graph
+    assert B.e2eg_sample_capacity(1000, 10, [5, 3]) == 10 * 5 + 50 * 3
+    assert B.e2eg_sample_capacity(20, 10, [5, 3]) == 10 * 5 + 20 * 3
+    assert B.e2eg_sample_capacity(20, 50, [5]) == 20 * 5
+    for bad in ([], [0], [5, 1 << 17], [2] * 9):
+        with pytest.raises(B.E2egError):
+            B.e2eg_sample_capacity(1000, 10, bad)
+    with pytest.raises(B.E2egError):
+        B.e2eg_sample_capacity(1 << 30, 1 << 30, [1 << 16])        # more draws than int32 holds
+    assert B.e2eg_sample_subgraph_workspace_bytes(1000, 10, [5, 3]) > 0
+    f = B.e2eg_sample_subgraph
+
+    def call(n_users=600, n=1000, nnz=5000, table=FAKE, val=None, n_seeds=10, seeds=FAKE, fanout=(5, 3), nodes=FAKE,
+             node_cap=1000, eu=FAKE, ei=FAKE, ew=None, edge_cap=200, ws=FAKE, wsb=big):
+        return status_of(B, f, n_users, n, nnz, FAKE, FAKE, table, val, n_seeds, seeds, list(fanout), 7, nodes, node_cap,
+                         eu, ei, ew, edge_cap, ws, wsb)
+
+    assert call(n_users=2000) == B.E2EG_ERR_INVALID_ARG
+    assert call(fanout=(5, 0)) == B.E2EG_ERR_INVALID_ARG
+    assert call(table=None) == B.E2EG_ERR_NULL_PTR
+    assert call(seeds=None) == B.E2EG_ERR_NULL_PTR
+    assert call(ew=FAKE) == B.E2EG_ERR_NULL_PTR                   # weights asked for, no values given
+    assert call(edge_cap=199) == B.E2EG_ERR_CAPACITY
+    assert call(node_cap=209) == B.E2EG_ERR_CAPACITY
+    assert call(wsb=64) == B.E2EG_ERR_WORKSPACE
+    assert f(600, 1000, 5000, FAKE, FAKE, FAKE, None, 0, None, [5, 3], 7, FAKE, 1000, FAKE, FAKE, None, 200, FAKE, big) == (0, 0, 0)
+
+
 def test_profile_aid_rejects_bad_arguments(B):
     assert status_of(B, B.e2eg_profile_begin, -1) == B.E2EG_ERR_INVALID_ARG
     assert status_of(B, B.e2eg_profile_copy, None, None, 16) == B.E2EG_ERR_NULL_PTR

@@ -31,17 +31,25 @@ def dev():
     return d
 
 
-def test_config3_full(dev, oracle):
+@pytest.fixture(scope="module")
+def config3(oracle):
+    """The 50 M-edge workload and the oracle's CSR of it, shared by the tests below."""
     t0 = time.time()
     c = make_config(3)
     progress(f"config 3 generated ({time.time() - t0:.0f}s)")
+    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
+    progress(f"oracle CSR built ({time.time() - t0:.0f}s)")
+    return c, row_ptr, col
+
+
+def test_config3_full(dev, oracle, config3):
+    t0 = time.time()
+    c, row_ptr, col = config3
     K, dt = c["K"], c["dtype"]
     u = torch.from_numpy(c["users"]).cuda()
     i = torch.from_numpy(c["items"]).cuda()
     g = dev.build_graph(c["n_users"], c["n_items"], u, i)
     del u, i
-    row_ptr, col = oracle.build_csr(c["n_users"], c["n_items"], c["users"], c["items"])
-    progress(f"oracle CSR built ({time.time() - t0:.0f}s)")
     assert g.nnz == col.size == 2 * c["n_edges"] + c["n"]
     assert np.array_equal(g.row_ptr.cpu().numpy().astype(np.int64), row_ptr)
     assert np.array_equal(g.col_idx.cpu().numpy(), col)
@@ -65,6 +73,76 @@ def test_config3_full(dev, oracle):
     scaleb = oracle.propagate_bwd(row_ptr, col, np.abs(oracle.as_f64(c["gY"])), K)
     comp, norm = assert_close(to_f64(gX0), refb, scaleb, dt, "bwd")
     progress(f"config 3 bwd: componentwise {comp:.2e} normwise {norm:.2e} ({time.time() - t0:.0f}s)")
+
+
+def test_config3_sampler_full(dev, oracle, config3):
+    """The importance sampler on the 50 M-edge graph, 4096 seed users, fan-outs (25, 10): the whole
+    sampling table and the whole sampled subgraph bit for bit.  The per-entry sampling weights are
+    seeded inputs given to both sides."""
+    from workloads import make_edge_weights
+    t0 = time.time()
+    c, row_ptr, col = config3
+    nu, ni = c["n_users"], c["n_items"]
+    g = dev.build_graph(nu, ni, torch.from_numpy(c["users"]).cuda(), torch.from_numpy(c["items"]).cuda())
+    p32 = make_edge_weights(col.size, seed=c["seed"] + 5000)
+    table = dev.sampler_table(g, p=torch.from_numpy(p32).cuda())
+    q = oracle.sampling_table(row_ptr, col, p32)
+    progress(f"sampling tables made ({time.time() - t0:.0f}s)")
+    got = table.view(torch.int64)[:g.nnz + 1].cpu().numpy().view(np.uint64)
+    assert got[0] == 0 and np.array_equal(got[1:], np.cumsum(q, dtype=np.uint64))
+    del got
+    seeds = np.sort(np.random.default_rng(c["seed"]).choice(nu, size=4096, replace=False)).astype(np.int32)
+    s = dev.sample_subgraph(g, table, torch.from_numpy(seeds).cuda(), [25, 10], seed=c["seed"], with_weights=False)
+    torch.cuda.synchronize()
+    r = oracle.sample_subgraph(nu, row_ptr, col, q, seeds, [25, 10], c["seed"])
+    progress(f"sampled {r['n_users']} users + {r['n_items']} items, {r['users'].size} picks ({time.time() - t0:.0f}s)")
+    assert (s["n_users"], s["n_items"]) == (r["n_users"], r["n_items"])
+    assert np.array_equal(s["nodes"].cpu().numpy(), r["nodes"])
+    assert np.array_equal(s["users"].cpu().numpy(), r["users"]) and np.array_equal(s["items"].cpu().numpy(), r["items"])
+
+
+def test_config3_weighted_full(dev, oracle, config3):
+    """Weighted edges at the stated size: entry values on sampled pairs located one by one in the
+    oracle's CSR, weighted degrees in full from plain sums over the pair list, and two properties of
+    the weighted operator on the GPU's outputs: D~^1/2 1 is a fixed point, and <A^ x, g> = <x, A^ g>."""
+    from workloads import make_edge_weights
+    t0 = time.time()
+    c, row_ptr, col = config3
+    nu, ni, n, K, F = c["n_users"], c["n_items"], c["n"], c["K"], c["F"]
+    users, items = c["users"], c["items"]
+    w = make_edge_weights(users.size, seed=c["seed"] + 4000)
+    g = dev.build_weighted_graph(nu, ni, torch.from_numpy(users).cuda(), torch.from_numpy(items).cuda(),
+                                 torch.from_numpy(w).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(g.col_idx.cpu().numpy(), col)
+    val = g.val.cpu().numpy()
+    rng = np.random.default_rng(7)
+    for e in rng.integers(0, users.size, size=4000):        # the pairs are distinct: each entry is its pair's weight
+        a, b = int(users[e]), nu + int(items[e])
+        pa = row_ptr[a] + np.searchsorted(col[row_ptr[a]:row_ptr[a + 1]], b)
+        pb = row_ptr[b] + np.searchsorted(col[row_ptr[b]:row_ptr[b + 1]], a)
+        assert col[pa] == b and col[pb] == a and val[pa] == w[e] and val[pb] == w[e]
+    diag = np.concatenate([row_ptr[:nu], row_ptr[nu + 1:] - 1])   # a user's row starts, an item's row ends with itself
+    assert np.array_equal(col[diag], np.arange(n)) and (val[diag] == 1.0).all()
+    deg = 1.0 + np.concatenate([np.bincount(users, weights=w.astype(np.float64), minlength=nu),
+                                np.bincount(items, weights=w.astype(np.float64), minlength=ni)])
+    got = g.deg_w.cpu().numpy().astype(np.float64)
+    assert np.abs(got - deg).max() <= 1e-6 * deg.max() and (np.abs(got - deg) <= 2e-7 * deg).all()
+    assert (np.abs(g.dinv_sqrt.cpu().numpy() * np.sqrt(deg) - 1.0) <= 3e-7).all()
+    progress(f"weighted values and degrees ok ({time.time() - t0:.0f}s)")
+    root = torch.from_numpy(np.sqrt(deg)).cuda().to(torch.float32)
+    X = (root[:, None] * torch.ones(1, F, device="cuda")).to(torch.bfloat16)
+    H = dev.propagate_fwd(g, X, K)
+    rel = ((H.float() - X.float()).abs() / X.float()).max().item()
+    assert rel <= TOL["bf16"], rel
+    x = to_device(c["X0"], "bf16")
+    gy = to_device(c["gY"], "bf16")
+    Ax = dev.propagate_fwd(g, x, 1).double()
+    Ag = dev.propagate_bwd(g, gy, 1).double()
+    lhs, rhs = (Ax * gy.double()).sum().item(), (x.double() * Ag).sum().item()
+    size = (Ax.abs() * gy.double().abs()).sum().item()
+    assert abs(lhs - rhs) <= 1e-3 * size, (lhs, rhs, size)
+    progress(f"weighted fixed point {rel:.2e}, adjoint identity {abs(lhs - rhs) / size:.2e} ({time.time() - t0:.0f}s)")
 
 
 def test_config4_full(dev, oracle):

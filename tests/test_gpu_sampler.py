@@ -1,0 +1,141 @@
+"""GPU parity of the importance sampler (Section 4.1: p(u->v) = w_uv^beta / sum_k w_uk^beta, at most
+k neighbours per node, depth L; Section 5, "Subgraph Sampling"): the integer sampling table and the
+sampled subgraph -- node list, pairs in pick order, weights -- bit for bit against the oracle on
+the same seeded graphs, weights and seeds; the powers w^beta to rounding."""
+import numpy as np
+import pytest
+import torch
+
+from parity import assert_close, to_device, to_f64
+from workloads import make_config, make_edge_weights, make_features, uniform_bipartite
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2511_20564_amd.device as d
+    d.B.load_library()
+    return d
+
+
+def parent(dev, oracle, nu, ni, users, items, w):
+    """The weighted parent graph on both sides."""
+    g = dev.build_weighted_graph(nu, ni, torch.from_numpy(np.ascontiguousarray(users, np.int32)).cuda(),
+                                 torch.from_numpy(np.ascontiguousarray(items, np.int32)).cuda(),
+                                 torch.from_numpy(np.ascontiguousarray(w, np.float32)).cuda())
+    row_ptr, col = oracle.build_csr(nu, ni, users, items)
+    val = oracle.edge_values(nu, users, items, w.astype(np.float64), row_ptr, col)
+    assert np.array_equal(g.val.cpu().numpy(), val.astype(np.float32))
+    return g, row_ptr, col, val
+
+
+def table_of(t, nnz):
+    return t.view(torch.int64)[:nnz + 1].cpu().numpy().view(np.uint64)
+
+
+def check_sample(dev, oracle, g, row_ptr, col, val, p32, seeds, fanout, seed):
+    table = dev.sampler_table(g, p=torch.from_numpy(p32).cuda())
+    q = oracle.sampling_table(row_ptr, col, p32)
+    cum = np.concatenate([[0], np.cumsum(q, dtype=np.uint64)]).astype(np.uint64)
+    assert np.array_equal(table_of(table, g.nnz), cum)
+    s = dev.sample_subgraph(g, table, torch.from_numpy(np.ascontiguousarray(seeds, np.int32)).cuda(), fanout, seed)
+    torch.cuda.synchronize()
+    r = oracle.sample_subgraph(g.n_users, row_ptr, col, q, seeds, fanout, seed)
+    assert (s["n_users"], s["n_items"]) == (r["n_users"], r["n_items"])
+    assert np.array_equal(s["nodes"].cpu().numpy(), r["nodes"])
+    assert np.array_equal(s["users"].cpu().numpy(), r["users"])
+    assert np.array_equal(s["items"].cpu().numpy(), r["items"])
+    assert np.array_equal(s["weights"].cpu().numpy(), val[r["entry"]].astype(np.float32))
+    return s, r
+
+
+@pytest.mark.parametrize("cfg,scale,n_seeds,fanout", [
+    (1, 1.0, 64, (5, 3)),
+    (1, 1.0, 200, (100,)),             # one hop, 100 neighbours: the paper's default setting
+    (2, 0.2, 512, (25, 10)),
+    (2, 0.2, 300, (4, 3, 2)),
+    (3, 0.02, 256, (25, 10)),
+])
+def test_sample_subgraph_matches_oracle(dev, oracle, cfg, scale, n_seeds, fanout):
+    c = make_config(cfg, scale=scale, features=False)
+    nu, ni = c["n_users"], c["n_items"]
+    w = make_edge_weights(c["users"].size, seed=10 + cfg)
+    g, row_ptr, col, val = parent(dev, oracle, nu, ni, c["users"], c["items"], w)
+    rng = np.random.default_rng(cfg)
+    p32 = val.astype(np.float32) ** np.float32(1.5)
+    seeds = rng.choice(nu, size=n_seeds, replace=False).astype(np.int32)
+    s, r = check_sample(dev, oracle, g, row_ptr, col, val, p32, seeds, list(fanout), seed=0xC0FFEE0000 + cfg)
+    print(f"config {cfg} x{scale} fan-out {fanout}: {r['n_users']} users, {r['n_items']} items, {r['users'].size} picks")
+    assert r["users"].size > n_seeds
+
+
+def test_sampler_edge_cases(dev, oracle):
+    """Seeds on the item side, a seed given twice, unusable weights, isolated seeds, a frontier capped
+    by the size of the graph."""
+    nu, ni, ne = 60, 25, 500
+    users, items = uniform_bipartite(nu, ni, ne, seed=4)
+    w = make_edge_weights(ne, seed=5)
+    w[::5] = 0.0
+    g, row_ptr, col, val = parent(dev, oracle, nu + 3, ni, users, items, w)      # users 60..62 have no edges
+    p32 = val.astype(np.float32)
+    p32[3::17] = np.nan
+    p32[5::19] = np.inf
+    p32[7::23] = 1e-30                                                            # far below the row maximum
+    seeds = np.array([62, 70, 3, 3, 64, 61, 10], np.int32)                        # users, items, repeats, isolated
+    check_sample(dev, oracle, g, row_ptr, col, val, p32, seeds, [3, 40, 2], seed=9)
+    check_sample(dev, oracle, g, row_ptr, col, val, p32, seeds[:1], [8], seed=9)  # only an isolated seed: no picks
+    check_sample(dev, oracle, g, row_ptr, col, val, p32, np.arange(nu + 3 + ni, dtype=np.int32), [50, 50], seed=1)
+    # the same call again gives the same subgraph, another seed another one
+    table = dev.sampler_table(g, p=torch.from_numpy(p32).cuda())
+    sd = torch.from_numpy(seeds).cuda()
+    a = dev.sample_subgraph(g, table, sd, [3, 4], 11)
+    b = dev.sample_subgraph(g, table, sd, [3, 4], 11)
+    c = dev.sample_subgraph(g, table, sd, [3, 4], 12)
+    assert torch.equal(a["users"], b["users"]) and torch.equal(a["items"], b["items"]) and torch.equal(a["nodes"], b["nodes"])
+    assert a["users"].numel() != c["users"].numel() or not (torch.equal(a["users"], c["users"]) and torch.equal(a["items"], c["items"]))
+    with pytest.raises(dev.B.E2egError) as e:
+        dev.sample_subgraph(g, table, torch.tensor([1, 88], dtype=torch.int32).cuda(), [3], 1)
+    assert e.value.status == dev.B.E2EG_ERR_BAD_INDEX
+
+
+@pytest.mark.parametrize("beta", [0.0, 1.0, 0.5, 1.7])
+def test_sampling_weights(dev, oracle, beta):
+    c = make_config(1, features=False)
+    w = make_edge_weights(c["users"].size, seed=2)
+    w[::6] = 0.0
+    g, row_ptr, col, val = parent(dev, oracle, c["n_users"], c["n_items"], c["users"], c["items"], w)
+    p = torch.empty(g.nnz, dtype=torch.float32, device="cuda")
+    dev.B.e2eg_sampling_weights(g.nnz, g.val, beta, p, torch.cuda.current_stream().cuda_stream)
+    got, ref = p.cpu().numpy().astype(np.float64), oracle.sampling_weights(val, beta)
+    assert np.array_equal(got == 0, ref == 0)
+    if beta in (0.0, 1.0):
+        assert np.array_equal(got, ref)
+    else:
+        assert np.abs(got - ref).max() <= 4e-7 * ref.max() and (np.abs(got - ref) <= 4e-7 * ref + 1e-30).all()
+
+
+def test_sampled_subgraph_through_the_path(dev, oracle):
+    """The sampler's output is the path's input: local pairs and weights -> CSR, weighted degrees,
+    two propagation layers, on both sides."""
+    c = make_config(2, scale=0.1, features=False)
+    nu, ni = c["n_users"], c["n_items"]
+    w = make_edge_weights(c["users"].size, seed=3)
+    g, row_ptr, col, val = parent(dev, oracle, nu, ni, c["users"], c["items"], w)
+    seeds = np.random.default_rng(5).choice(nu, size=128, replace=False).astype(np.int32)
+    s, r = check_sample(dev, oracle, g, row_ptr, col, val, val.astype(np.float32), seeds, [25, 10], seed=21)
+    sub = dev.build_weighted_graph(s["n_users"], s["n_items"], s["users"], s["items"], s["weights"])
+    rw = val[r["entry"]]
+    rp, cl = oracle.build_csr(r["n_users"], r["n_items"], r["users"], r["items"])
+    vl = oracle.edge_values(r["n_users"], r["users"], r["items"], rw, rp, cl)
+    assert np.array_equal(sub.col_idx.cpu().numpy(), cl) and np.array_equal(sub.val.cpu().numpy(), vl.astype(np.float32))
+    F, K, dt = 64, 2, "bf16"
+    n_local = r["n_users"] + r["n_items"]
+    Xh = make_features(n_local, F, 0.1, 7, dt)
+    H = dev.propagate_fwd(sub, to_device(Xh, dt), K)
+    torch.cuda.synchronize()
+    ref = oracle.propagate_weighted(rp, cl, vl, Xh, K)
+    scale = oracle.propagate_weighted(rp, cl, vl, np.abs(oracle.as_f64(Xh)), K)
+    assert_close(to_f64(H), ref, scale, dt, "propagation on the sampled subgraph")
