@@ -2,6 +2,9 @@
 
  * 50 M-edge graph: CSR bit-exact against the oracle's, all K layers forward and the backward
    against the full fp64 oracle.
+ * on the same graph: the importance sampler's table and a two-hop subgraph bit for bit; the weighted
+   path's values (sampled pairs), weighted degrees (in full) and two operator properties.
+ * a 17 M-node graph (more rows than 24-bit offsets reach) against the full oracle.
  * the sampled mini-batch drawn from that graph: staged pipeline checks.
  * 500 M-edge graph: degrees / row_ptr bit-exact in full; column lists bit-exact and every layer
    (teacher-forced from the GPU's previous layer) within tolerance on sampled rows computed one
@@ -143,6 +146,40 @@ def test_config3_weighted_full(dev, oracle, config3):
     size = (Ax.abs() * gy.double().abs()).sum().item()
     assert abs(lhs - rhs) <= 1e-3 * size, (lhs, rhs, size)
     progress(f"weighted fixed point {rel:.2e}, adjoint identity {abs(lhs - rhs) / size:.2e} ({time.time() - t0:.0f}s)")
+
+
+def test_more_than_2_to_24_nodes(dev, oracle):
+    """17 M nodes: past the size up to which the gather kernel forms 32-bit row offsets with a 24-bit
+    multiply, so the 64-bit instantiation runs.  Narrow rows (fp32, F=8) keep the case small enough
+    for the full oracle; a few items with 10^5 users give it split and windowed rows as well."""
+    from workloads import make_features, uniform_bipartite
+    t0 = time.time()
+    nu, ni, ne, F, K = 16_300_000, 700_000, 18_000_000, 8, 2
+    users, items = uniform_bipartite(nu, ni, ne, seed=24)
+    rng = np.random.default_rng(24)
+    hu = rng.integers(0, nu, size=4 * 100_000).astype(np.int32)
+    users = np.concatenate([users, hu])
+    items = np.concatenate([items, np.repeat(np.arange(4, dtype=np.int32), 100_000)])
+    n = nu + ni
+    assert n + 1 > 1 << 24
+    progress(f"17 M-node graph generated ({time.time() - t0:.0f}s)")
+    g = dev.build_graph(nu, ni, torch.from_numpy(users).cuda(), torch.from_numpy(items).cuda())
+    row_ptr, col = oracle.build_csr(nu, ni, users, items)
+    assert np.array_equal(g.row_ptr.cpu().numpy().astype(np.int64), row_ptr) and np.array_equal(g.col_idx.cpu().numpy(), col)
+    progress(f"structure ok, nnz={g.nnz} ({time.time() - t0:.0f}s)")
+    Xh, gh = make_features(n, F, 0.1, 1, "f32"), make_features(n, F, 1.0, 2, "f32")
+    H = dev.propagate_fwd(g, torch.from_numpy(Xh).cuda(), K, all_layers=True)
+    G0 = dev.propagate_bwd(g, torch.from_numpy(gh).cuda(), K)
+    torch.cuda.synchronize()
+    ref = oracle.propagate_fwd(row_ptr, col, Xh, K)
+    scale = oracle.propagate_fwd(row_ptr, col, np.abs(Xh).astype(np.float64), K)
+    for k in range(K):
+        comp, norm = assert_close(to_f64(H[k]), ref[k], scale[k], "f32", f"layer {k + 1}")
+    del ref, scale
+    refb = oracle.propagate_bwd(row_ptr, col, gh, K)
+    scaleb = oracle.propagate_bwd(row_ptr, col, np.abs(gh).astype(np.float64), K)
+    compb, _ = assert_close(to_f64(G0), refb, scaleb, "f32", "bwd")
+    progress(f"17 M nodes: fwd {comp:.2e}, bwd {compb:.2e} (tol {TOL['f32']}) ({time.time() - t0:.0f}s)")
 
 
 def test_config4_full(dev, oracle):
