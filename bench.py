@@ -54,7 +54,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1",
+        print("bench.py: the library is single-GPU (no sharding, no collectives); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
@@ -196,10 +196,18 @@ def main():
     for r in range(10):
         sub = dev.sample_subgraph(gw, table, seeds_t, fan, 2 + r, ws=sws)
     sample_ms = (time.perf_counter() - t1) / 10 * 1e3
+    # ... and what the sampled pairs need before the path can run on them: CSR, weighted degrees, schedule
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for r in range(10):
+        gs = dev.build_weighted_graph(sub["n_users"], sub["n_items"], sub["users"], sub["items"], sub["weights"])
+    torch.cuda.synchronize()
+    subgraph_ms = (time.perf_counter() - t1) / 10 * 1e3
     sampler = {"table_ms": round(table_ms, 3), "sample_ms": round(sample_ms, 4), "seeds": 4096, "fanout": fan,
                "picks": int(sub["users"].numel()), "nodes": int(sub["n_users"] + sub["n_items"]),
-               "Mpicks_per_s": round(sub["users"].numel() / sample_ms / 1e3, 2)}
-    del gw, table, sws, sub
+               "Mpicks_per_s": round(sub["users"].numel() / sample_ms / 1e3, 2),
+               "subgraph_csr_and_schedule_ms": round(subgraph_ms, 4), "subgraph_nnz": int(gs.nnz)}
+    del gw, table, sws, sub, gs
 
     # the dense per-layer update on the matrix cores at the mini-batch shape (about 200 k sampled
     # nodes, 128 x 128 weights): forward, and backward (dP and dW); flops and bytes are algorithmic

@@ -66,6 +66,10 @@ void profile_mark(hipStream_t stream, bool after);
 size_t scan_workspace_bytes(int64_t count);
 hipError_t exclusive_scan_i32(const int32_t* in, int32_t* out, int64_t count, int32_t* d_total,
                               void* ws, hipStream_t stream);
+// Up to 8 arrays of `count` values each in one set of launches (in[y] == out[y] allowed); `ws` needs
+// k * scan_workspace_bytes(count).
+hipError_t exclusive_scan_i32_batch(const int32_t* const* in, int32_t* const* out, int k, int64_t count, void* ws,
+                                    hipStream_t stream);
 // The same over uint64 (sums must stay below 2^64); `ws` needs scan_u64_workspace_bytes(count).
 size_t scan_u64_workspace_bytes(int64_t count);
 hipError_t exclusive_scan_u64(const uint64_t* in, uint64_t* out, int64_t count, uint64_t* d_total,

@@ -25,7 +25,8 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// Per node: degree, d^-1/2, and the sort key (larger degree first, then node id).
+// Per node: degree, d^-1/2, and the sort key (larger degree first, then node id): n - d in the
+// upper half, which needs bits_for(n + 1) bits, so small graphs sort in few passes.
 __global__ void row_stats(const int32_t* __restrict__ row_ptr, int64_t n, int32_t* __restrict__ deg,
                           float* __restrict__ dinv_sqrt, uint64_t* __restrict__ keys) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -33,7 +34,7 @@ __global__ void row_stats(const int32_t* __restrict__ row_ptr, int64_t n, int32_
     const int32_t d = row_ptr[i + 1] - row_ptr[i];
     if (deg) deg[i] = d;
     dinv_sqrt[i] = d > 0 ? (float)(1.0 / sqrt((double)d)) : 0.0f;
-    keys[i] = ((uint64_t)(uint32_t)(0x7fffffff - d) << 32) | (uint32_t)i;
+    keys[i] = ((uint64_t)(uint32_t)(d > n ? 0 : (int32_t)n - d) << 32) | (uint32_t)i;
 }
 
 // Sorted (degree, node) keys -> is the node one of the kTopNodes most popular, and its rank.
@@ -86,7 +87,8 @@ __global__ void permute_nodes(const int32_t* __restrict__ rank_of, const int32_t
     nslot[p] = (d > kSegLen && !wide) ? segs : 0;    // those of them that are partial-sum slots
     is_short[p] = d <= kShortMax ? 1 : 0;
     is_multi[p] = d > kSegLen ? 1 : 0;
-    const uint32_t hi = d > kShortMax ? 0x7fffffffu : (((uint32_t)p / kSortBlock) << 8) | (uint32_t)d;
+    // longer rows sort behind every short one: one block number past the last
+    const uint32_t hi = d > kShortMax ? ((uint32_t)(n / kSortBlock) + 1u) << 8 : (((uint32_t)p / kSortBlock) << 8) | (uint32_t)d;
     short_keys[p] = ((uint64_t)hi << 32) | (uint32_t)p;
 }
 
@@ -170,16 +172,18 @@ __global__ void emit_rows(RowScans sc, const int32_t* __restrict__ pair_off, int
     }
 }
 
-// Sort key of a segment: slotted segments by first column, then the one-segment rows in order.
-__device__ __forceinline__ uint64_t segment_key(const SchedView& s, const Segment& g, int32_t t) {
-    return g.slot >= 0 ? ((uint64_t)(uint32_t)s.zcol[g.beg] << 32) | (uint32_t)t
-                       : (1ull << 63) | ((uint64_t)(uint32_t)t << 32) | (uint32_t)t;
+// Sort key of a segment (upper half; the lower half is the segment's number t, which is also its
+// place in the key array, so the stable sort keeps equal keys in order of t): slotted segments by
+// first column, then the one-segment rows, which all carry 2^bits with bits = bits_for(n).
+__device__ __forceinline__ uint64_t segment_key(const SchedView& s, const Segment& g, int32_t t, int bits) {
+    const uint32_t hi = g.slot >= 0 ? (uint32_t)s.zcol[g.beg] : 1u << bits;
+    return ((uint64_t)hi << 32) | (uint32_t)t;
 }
 
 // Segments of rows cut by length only.  One thread per segment t: find its row (binary search in
 // seg_off, the ascending first segment number of every row; rows without such segments repeat
 // their successor's number and are skipped by taking the last row whose number is <= t).
-__global__ void emit_plain_segments(SchedView s, RowScans sc, int64_t n, Segment* __restrict__ seg_tmp,
+__global__ void emit_plain_segments(SchedView s, RowScans sc, int64_t n, int bits, Segment* __restrict__ seg_tmp,
                                     uint64_t* __restrict__ keys) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= sc.seg_off[n]) return;
@@ -195,11 +199,11 @@ __global__ void emit_plain_segments(SchedView s, RowScans sc, int64_t n, Segment
     const int32_t end = beg + kSegLen < row_end ? beg + kSegLen : row_end;
     const Segment g{row, beg, end, row_end - row_beg > kSegLen ? sc.slot_off[row] + q : -1};
     seg_tmp[t] = g;
-    keys[t] = segment_key(s, g, (int32_t)t);
+    keys[t] = segment_key(s, g, (int32_t)t, bits);
 }
 
 // Segments of wide rows: one thread per (row, window) cuts that run by length.
-__global__ void emit_wide_segments(SchedView s, RowScans sc, int64_t n, int32_t wide_rows, int32_t nwin,
+__global__ void emit_wide_segments(SchedView s, RowScans sc, int64_t n, int bits, int32_t wide_rows, int32_t nwin,
                                    const int32_t* __restrict__ bounds, const int32_t* __restrict__ pair_off,
                                    Segment* __restrict__ seg_tmp, uint64_t* __restrict__ keys) {
     const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -213,7 +217,7 @@ __global__ void emit_wide_segments(SchedView s, RowScans sc, int64_t n, int32_t 
     for (int32_t beg = run_beg; beg < run_end; beg += kSegLen, ++q) {
         const Segment g{p, beg, beg + kSegLen < run_end ? beg + kSegLen : run_end, slot0 + q};
         seg_tmp[t0 + q] = g;
-        keys[t0 + q] = segment_key(s, g, t0 + q);
+        keys[t0 + q] = segment_key(s, g, t0 + q, bits);
     }
 }
 
@@ -358,7 +362,7 @@ NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     w.pair_nseg = c.take<int32_t>(sched_max_pairs(n) + 1);
     w.seg_len = c.take<int32_t>(max_seg + 1);
     w.seg_tmp = c.take<Segment>(max_seg);
-    w.scan_ws = c.take<char>(scan_workspace_bytes(m));
+    w.scan_ws = c.take<char>(5 * scan_workspace_bytes(m));   // the five row scans share one set of launches
     w.sort_ws = c.take<char>(radix_sort_workspace_bytes(m));
     w.bytes = c.size();
     return w;
@@ -417,7 +421,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
     if (n > 0) {
         row_stats<<<grid_for(n), blk, 0, stream>>>(d_row_ptr, n, d_deg, d_dinv_sqrt, src);
         E2EG_LAUNCH_CHECK("row_stats");
-        int32_t st = radix_sort_u64(&src, &dst, n, 32, 32, w.sort_ws, stream);
+        int32_t st = radix_sort_u64(&src, &dst, n, 32, bits_for((int64_t)n + 1), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
     }
     mark_top<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(src, n, w.rank_of, w.not_top);
@@ -433,16 +437,16 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
                                                                w.is_short, w.is_multi, src);
     E2EG_LAUNCH_CHECK("permute_nodes");
     if (n > 0) {  // short rows: by block of kSortBlock rows, then by length
-        int32_t st = radix_sort_u64(&src, &dst, n, 32, 32, w.sort_ws, stream);
+        int32_t st = radix_sort_u64(&src, &dst, n, 32, 8 + bits_for(n / kSortBlock + 2), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
         place_short_rows<<<grid_for(n), blk, 0, stream>>>(src, n, view);
         E2EG_LAUNCH_CHECK("place_short_rows");
     }
-    E2EG_HIP_TRY(exclusive_scan_i32(w.zdeg, view.zrow_ptr, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.nseg, w.nseg, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.nslot, w.nslot, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.is_short, w.is_short, (int64_t)n + 1, nullptr, w.scan_ws, stream));
-    E2EG_HIP_TRY(exclusive_scan_i32(w.is_multi, w.is_multi, (int64_t)n + 1, nullptr, w.scan_ws, stream));
+    {  // five prefix sums over the internal rows, one set of launches
+        const int32_t* const in[5] = {w.zdeg, w.nseg, w.nslot, w.is_short, w.is_multi};
+        int32_t* const out[5] = {view.zrow_ptr, w.nseg, w.nslot, w.is_short, w.is_multi};
+        E2EG_HIP_TRY(exclusive_scan_i32_batch(in, out, 5, (int64_t)n + 1, w.scan_ws, stream));
+    }
 
     // 2. the CSR in internal ids
     if (nnz > 0) {
@@ -475,14 +479,15 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         dst = w.keys_b;
         fill_keys<<<grid_for(view.max_seg), blk, 0, stream>>>(src, view.max_seg);
         E2EG_LAUNCH_CHECK("fill_keys");
-        emit_plain_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(view, sc, n, w.seg_tmp, src);
+        const int bits = bits_for(n);  // columns are below 2^bits; 2^bits marks one-segment rows, all ones padding
+        emit_plain_segments<<<grid_for(view.max_seg), blk, 0, stream>>>(view, sc, n, bits, w.seg_tmp, src);
         E2EG_LAUNCH_CHECK("emit_plain_segments");
         if (pairs > 0) {
-            emit_wide_segments<<<grid_for(pairs), blk, 0, stream>>>(view, sc, n, wide_rows, nwin, w.bounds,
+            emit_wide_segments<<<grid_for(pairs), blk, 0, stream>>>(view, sc, n, bits, wide_rows, nwin, w.bounds,
                                                                    w.pair_nseg, w.seg_tmp, src);
             E2EG_LAUNCH_CHECK("emit_wide_segments");
         }
-        int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, 32, w.sort_ws, stream);
+        int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, bits + 2 < 32 ? bits + 2 : 32, w.sort_ws, stream);
         if (st != E2EG_OK) return st;
         place_segments<<<grid_for(view.max_seg + 1), blk, 0, stream>>>(src, w.seg_tmp, view, w.seg_len);
         E2EG_LAUNCH_CHECK("place_segments");

@@ -9,8 +9,12 @@ constexpr int kThreads = 256;
 constexpr int kSortItems = 8;
 constexpr int kSortTile = kThreads * kSortItems;  // keys per block
 constexpr int kWaves = kThreads / 64;
+constexpr int kFusedBlocks = 128;  // up to this many blocks the scatter adds up its offsets itself
 
 // ---- radix sort, one 8-bit digit per pass --------------------------------------------------
+// The table is digit-major [256][nblocks] for the scan, or (BLOCK_MAJOR) [nblocks][256] for a
+// scatter that adds up its offsets itself.
+template <bool BLOCK_MAJOR>
 __global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __restrict__ keys,
                                                            int64_t count, int shift,
                                                            int32_t* __restrict__ hist,
@@ -25,18 +29,24 @@ __global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __res
         if (idx < count) atomicAdd(&h[(int)((keys[idx] >> shift) & 255)], 1);
     }
     __syncthreads();
-    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+    if (BLOCK_MAJOR) hist[(int64_t)blockIdx.x * 256 + threadIdx.x] = h[threadIdx.x];
+    else hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
 }
 
 // Stable scatter.  A block's tile is split into one contiguous chunk per wavefront; a wavefront
 // walks its chunk 64 keys at a time, ranking equal digits by lane order plus a running
 // per-wavefront digit count, so ranks follow input order.
+// `offs` is the digit-major table [256][nblocks] of scanned offsets, or, with COUNTS, the raw
+// block-major histogram [nblocks][256], from which every workgroup then adds up its own 256
+// offsets (few blocks: a short loop of coalesced reads that saves the launches of a scan).
+template <bool COUNTS>
 __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restrict__ in,
                                                          uint64_t* __restrict__ out,
                                                          int64_t count, int shift,
                                                          const int32_t* __restrict__ offs,
                                                          int32_t nblocks) {
     __shared__ int wave_cnt[kWaves][256];
+    __shared__ int wave_tot[kWaves];
     for (int k = threadIdx.x; k < kWaves * 256; k += kThreads) (&wave_cnt[0][0])[k] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63;
@@ -64,9 +74,35 @@ __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restr
         if (valid && below == 0) wave_cnt[wave][d] = pre + __popcll(peers);
     }
     __syncthreads();
+    int base;
+    if (COUNTS) {
+        // keys with a smaller digit anywhere, plus keys with this digit in earlier blocks
+        int before = 0, total = 0;
+        const int32_t* col = offs + threadIdx.x;
+#pragma unroll 16
+        for (int b = 0; b < nblocks; ++b) {
+            const int c = col[(int64_t)b * 256];
+            if (b < (int)blockIdx.x) before += c;
+            total += c;
+        }
+        int inc = total;  // inclusive scan over the 256 digits: within the wavefront, then across the four
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const int t = __shfl_up(inc, dlt, 64);
+            if (lane >= dlt) inc += t;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int lower = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+            if (w < wave) lower += wave_tot[w];
+        base = lower + inc - total + before;
+    } else {
+        base = offs[(int64_t)threadIdx.x * nblocks + blockIdx.x];
+    }
     {
         const int d = threadIdx.x;
-        int base = offs[(int64_t)d * nblocks + blockIdx.x];
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             int c = wave_cnt[w][d];
@@ -99,10 +135,16 @@ int32_t radix_sort_u64(uint64_t** src, uint64_t** dst, int64_t count, int lo, in
     int32_t* hist = static_cast<int32_t*>(ws);
     void* scan_ws = static_cast<char*>(ws) + align_up((size_t)(256 * (int64_t)nblocks) * sizeof(int32_t));
     for (int shift = lo; shift < lo + nbits; shift += 8) {
-        sort_histogram<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, hist, nblocks);
-        E2EG_LAUNCH_CHECK("sort_histogram");
-        E2EG_HIP_TRY(exclusive_scan_i32(hist, hist, (int64_t)256 * nblocks, nullptr, scan_ws, stream));
-        sort_scatter<<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift, hist, nblocks);
+        if (nblocks <= kFusedBlocks) {
+            sort_histogram<true><<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, hist, nblocks);
+            E2EG_LAUNCH_CHECK("sort_histogram");
+            sort_scatter<true><<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift, hist, nblocks);
+        } else {
+            sort_histogram<false><<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, count, shift, hist, nblocks);
+            E2EG_LAUNCH_CHECK("sort_histogram");
+            E2EG_HIP_TRY(exclusive_scan_i32(hist, hist, (int64_t)256 * nblocks, nullptr, scan_ws, stream));
+            sort_scatter<false><<<dim3(nblocks), dim3(kThreads), 0, stream>>>(*src, *dst, count, shift, hist, nblocks);
+        }
         E2EG_LAUNCH_CHECK("sort_scatter");
         uint64_t* t = *src;
         *src = *dst;

@@ -12,16 +12,18 @@ os.environ.setdefault("E2EG_WORKLOAD_CACHE", "/tmp/e2eg_workload_cache")
 
 
 def progress(msg: str) -> None:
-    """Progress line for long GPU tests: to the real stderr (not captured) and to a log file."""
+    """Progress line for long GPU tests: to the real stderr (not captured) and, if the environment
+    names one in E2EG_PROGRESS_LOG, appended to that file."""
     line = f"[test] {msg}"
     print(line, file=sys.__stderr__, flush=True)
-    try:
-        out = os.path.join(ROOT, "gpurun_out")
-        os.makedirs(out, exist_ok=True)
-        with open(os.path.join(out, "test_progress.log"), "a") as f:
-            f.write(line + "\n")
-    except OSError:
-        pass
+    path = os.environ.get("E2EG_PROGRESS_LOG", "")
+    if path:
+        try:
+            os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+            with open(path, "a") as f:
+                f.write(line + "\n")
+        except OSError:
+            pass
 
 
 def pytest_configure(config):
