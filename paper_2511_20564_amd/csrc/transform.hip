@@ -66,11 +66,12 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     const int ldb = kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
     const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
-    // stage the weight tile, k contiguous per output column
+    // stage the weight tile, k contiguous per output column.  Transposing: consecutive lanes take
+    // consecutive k, so that their 2-byte LDS writes fall into consecutive banks.
     if (TRANS_W) {
         const int cvecs = ng / 8;
         for (int e = threadIdx.x; e < kdim * cvecs; e += kThreads) {
-            const int k = e / cvecs, cv = e - k * cvecs;
+            const int cv = e / kdim, k = e - cv * kdim;
             const uint4 q = *reinterpret_cast<const uint4*>(w + (int64_t)k * w_ld + n0 + cv * 8);
             const uint32_t words[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -169,8 +170,10 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
     const int khalf = lane >> 5;
-    const int cv = threadIdx.x & 15;   // 8-column chunk this thread stages
-    const int tr = threadIdx.x >> 4;   // tile row 0..15 (and +16)
+    // staging: consecutive lanes take consecutive tile rows (their 2-byte writes into the
+    // transposed tiles then fall into consecutive banks); a thread stages two 8-column chunks
+    const int lr = threadIdx.x & 31;   // tile row
+    const int cq = threadIdx.x >> 5;   // 8-column chunk cq (and cq + 8)
     const int oblocks = og / 32;
     const bool wave_live = wave * 32 < cg;
 
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            const int lr = tr + half * 16;
+            const int cv = cq + half * 8;
             const int64_t r = r0 + lr;
             uint4 qp = make_uint4(0u, 0u, 0u, 0u), qz = qp;
             if (r < r_end) {
@@ -247,8 +250,10 @@ __global__ __launch_bounds__(kThreads) void weight_grad_reduce(const float* __re
     const int j = threadIdx.x % kReduceElems, q = threadIdx.x / kReduceElems;
     const int e = blockIdx.x * kReduceElems + j;
     double s = 0.0;
-    if (e < count)
+    if (e < count) {
+#pragma unroll 8
         for (int32_t b = q; b < nblocks; b += kReduceSlices) s += (double)partial[(int64_t)b * count + e];
+    }
     red[q][j] = s;
     __syncthreads();
     if (q == 0 && e < count) {
