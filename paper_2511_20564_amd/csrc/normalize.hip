@@ -5,19 +5,22 @@
 // degree (ties in node order); all other nodes follow in node order.  The CSR is rewritten in
 // internal ids, rows in internal order, columns ascending.  What this buys on a power-law
 // user-item graph:
-//   - "is this neighbour popular" is one compare, and the feature rows of the most popular
-//     nodes are one contiguous block (the propagation kernel stages it in LDS);
-//   - every neighbour list starts with its popular entries;
+//   - the feature rows of the most popular nodes are one contiguous block, and every neighbour
+//     list starts with its popular entries;
 //   - everything else keeps the caller's node order (users, then items), so at any time the
 //     whole GPU gathers from the same side of the graph and the L2 caches hold one hot set.
 // Rows of at most kShortMax entries are listed ordered by length inside blocks of kSortBlock
 // consecutive rows (the kernel sums several of them side by side, so neighbours in the list should
 // be equally long, while the block-wise order keeps the users-then-items progression).  Longer
-// rows are cut into segments of kSegLen entries; the segments of rows with several are ordered by
-// first column, so that segments which read the same stretch of feature rows can be run at the
-// same time on the same L2 (the kernel deals the ordered list out to the XCDs in contiguous
-// eighths); rows of one segment follow in row order.
-// All of it is integer work: radix sorts and scans.  Nothing here depends on the feature width.
+// rows are cut into segments of kSegLen entries, the very longest ones first at the boundaries
+// of windows of kWindow internal ids; the segments of rows with several are ordered by first
+// column, so that segments which read the same stretch of feature rows can be run at the same
+// time on the same L2 (the list is dealt out to the XCDs in contiguous stretches of equal entry
+// counts); rows of one segment follow in row order.
+// All of it is integer work: radix sorts and scans, with sort keys only as wide as the graph
+// needs, so that a small (sampled) graph costs few launches.  Nothing here depends on the feature
+// width.  For a weighted graph (e2eg_normalize_weighted) d~ is the sum of the row's values and
+// the values are carried into the schedule in the order of its column indices.
 #include "common.h"
 
 namespace e2eg {

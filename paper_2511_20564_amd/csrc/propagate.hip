@@ -27,6 +27,11 @@
 //     lanes, and the per-row work (bounds, scale, conversion, store) is paid once per 64/G rows;
 //     on a power-law graph most rows are short and this per-row work, not memory, was what bound
 //     the first version of the kernel (vector-ALU issue).
+// On a weighted graph (e2eg_propagate_weighted_*) the schedule also holds the entries' values, in
+// the order of its own column indices; the WEIGHTED instantiation of the kernel loads them beside
+// the indices (same predicates), hands them to the lanes by the same shuffles, and replaces the
+// add of a gathered row by a multiply-add.  e2eg_aggregate is the same kernel with other per-row
+// scales (mean, transposed mean, plain sum) and an optional addend.
 // Measured on gfx950: the dot-product instruction v_dot2c_f32_bf16 with unit weights adds a
 // bf16 pair in one instruction instead of shift + add per element, but ran slower than the plain
 // sequence, and capping registers for more resident wavefronts cost more in spills than it gained;
@@ -370,7 +375,7 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
 constexpr int kShortPerWave = 8;   // short rows a wavefront works through, 64/G at a time
-constexpr int kSingleBlocksPerXcd = 512;
+constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when the graph cannot have that many such rows)
 
 // Three kinds of workgroup.
 // A. Segments of rows cut into several (the first n_slot entries of the ordered segment list,
@@ -527,8 +532,10 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
 
 constexpr int kPrescaleThreads = 256;
 
-// Z(0) = S X(0) in internal row order: one streaming pass, 16 bytes per thread.  Also clears the
-// zero rows (index n) of both Z buffers.
+constexpr int kPrescaleRows = 4;   // rows per thread: their dependent loads (row -> node -> x, s) overlap
+
+// Z(0) = S X(0) in internal row order: one streaming pass, 16 bytes of kPrescaleRows rows per
+// thread.  Also clears the zero rows (index n) of both Z buffers.
 template <typename T>
 __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename T::elem* __restrict__ x,
                                                                    int64_t ldx,
@@ -540,23 +547,37 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
     constexpr int V = T::kVec;
     const int chunks = F / V;
     const int64_t id = (int64_t)blockIdx.x * kPrescaleThreads + threadIdx.x;
-    if (id >= (n + 1) * chunks) return;
-    const int64_t zrow = id / chunks;
-    const int col = (int)(id - zrow * chunks) * V;
-    float v[V];
-    if (zrow == n) {
+    const int64_t groups = (n + 1 + kPrescaleRows - 1) / kPrescaleRows;
+    if (id >= groups * chunks) return;
+    const int64_t group = id / chunks;
+    const int col = (int)(id - group * chunks) * V;
+    int64_t node[kPrescaleRows];
 #pragma unroll
-        for (int k = 0; k < V; ++k) v[k] = 0.0f;
-        store_vec<T>(z + zrow * F + col, v);
-        if (z_other) store_vec<T>(z_other + zrow * F + col, v);
-        return;
+    for (int i = 0; i < kPrescaleRows; ++i) {
+        const int64_t zrow = group * kPrescaleRows + i;
+        node[i] = zrow < n ? orig[zrow] : -1;
     }
-    const int64_t node = orig[zrow];
-    load_vec<T>(x + node * ldx + col, v);
-    const float s = dinv_sqrt[node];
+    float v[kPrescaleRows][V];
+    float s[kPrescaleRows];
 #pragma unroll
-    for (int k = 0; k < V; ++k) v[k] *= s;
-    store_vec<T>(z + zrow * F + col, v);
+    for (int i = 0; i < kPrescaleRows; ++i) {
+        s[i] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[i][k] = 0.0f;
+        if (node[i] >= 0) {
+            load_vec<T>(x + node[i] * ldx + col, v[i]);
+            s[i] = dinv_sqrt[node[i]];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPrescaleRows; ++i) {
+        const int64_t zrow = group * kPrescaleRows + i;
+        if (zrow > n) continue;
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[i][k] *= s[i];   // the zero row: 0 * 0
+        store_vec<T>(z + zrow * F + col, v[i]);
+        if (zrow == n && z_other) store_vec<T>(z_other + zrow * F + col, v[i]);
+    }
 }
 
 template <typename T, bool NARROW, bool WEIGHTED>
@@ -583,7 +604,8 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
     // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs
     const int64_t a_blocks = nnz > kSegLen ? ceil_div(ceil_div(sched_max_slot(n, nnz), kWaves), kXcds) + 1 : 0;
-    const int64_t b_blocks = nnz > kShortMax ? kSingleBlocksPerXcd : 0;
+    int64_t b_blocks = nnz > kShortMax ? ceil_div(ceil_div(sched_max_plain(nnz), kWaves), kXcds) + 1 : 0;
+    if (b_blocks > kSingleBlocksPerXcd) b_blocks = kSingleBlocksPerXcd;
     const int64_t c_blocks = ceil_div(ceil_div(n, kWaves * kShortPerWave), kXcds) + 1;
     a.n = (int32_t)n;
     a.a_blocks = (int32_t)a_blocks;
@@ -662,7 +684,7 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     const int chunks = F / T::kVec;
     E* z_cur = static_cast<E*>(w.z[0]);
     E* z_next = static_cast<E*>(w.z[1]);
-    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kPrescaleThreads)),
+    prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig, z_cur,
                                                             z_next, n, F);
     E2EG_LAUNCH_CHECK("prescale_rows");
@@ -734,7 +756,7 @@ int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_p
                                                                                 w.scale_out);
     E2EG_LAUNCH_CHECK("aggregate_scales");
     const int chunks = F / T::kVec;
-    prescale_rows<T><<<dim3((unsigned)ceil_div(((int64_t)n + 1) * chunks, kPrescaleThreads)),
+    prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(x), ldx, w.scale_in, view.orig,
                                                             static_cast<E*>(w.z), nullptr, n, F);
     E2EG_LAUNCH_CHECK("prescale_rows");
