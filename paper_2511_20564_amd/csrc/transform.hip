@@ -34,10 +34,13 @@ __device__ __forceinline__ f32x16 mfma(const uint4 a, const uint4 b, const f32x1
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two floats -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Keep the bf16 halves of g where the matching half of h is > 0.
@@ -55,7 +58,12 @@ __device__ __forceinline__ uint4 mask_vec(uint4 g, uint4 h) {
 // when MASKED), B(c, k) = TRANS_W ? w[k][c] : w[c][k].
 // grid.x: blocks of `tiles` x 128 rows (the weight tile is staged once per workgroup and serves
 // all its row tiles); grid.y: groups of `ngroup` output columns.
-template <bool MASKED, bool TRANS_W, bool RELU>
+// KS: the most k-steps of 16 a row can have (8 for up to 128 input columns).  A wavefront requests
+// the rows of its next tile before it multiplies the current one, so that the loads overlap the
+// product and the stores.
+// EXACT: kdim == 16 * KS and every workgroup has 128 output columns, so that the loops over
+// k-steps and column blocks have constant bounds and compile to straight-line code.
+template <bool MASKED, bool TRANS_W, bool RELU, int KS, bool EXACT>
 __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restrict__ a_rows,
                                                        const uint16_t* __restrict__ mask_rows,
                                                        const uint16_t* __restrict__ w,
@@ -94,31 +102,41 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
     const int khalf = lane >> 5;
-    const int ksteps = kdim / 16;
-    const int nblocks = ng / 32;
+    const int ksteps = EXACT ? KS : kdim / 16;
+    const int nblocks = EXACT ? 4 : ng / 32;
+    // rows of one tile as this lane feeds them to the matrix core (zeros past the end)
+    auto load_rows = [&](int64_t r, uint4 (&va)[KS], uint4 (&vm)[MASKED ? KS : 1]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            va[ks] = make_uint4(0u, 0u, 0u, 0u);
+            if (MASKED) vm[ks] = make_uint4(0u, 0u, 0u, 0u);
+            if (ks < ksteps && r < n) {
+                const int64_t at = r * kdim + ks * 16 + khalf * 8;
+                va[ks] = *reinterpret_cast<const uint4*>(a_rows + at);
+                if (MASKED) vm[ks] = *reinterpret_cast<const uint4*>(mask_rows + at);
+            }
+        }
+    };
+    const int64_t row_first = (int64_t)blockIdx.x * tiles * kRowsPerBlock + wave * 32 + l32;
+    uint4 nxt_a[KS], nxt_m[MASKED ? KS : 1];
+    load_rows(row_first, nxt_a, nxt_m);
 #pragma unroll 1
     for (int tile = 0; tile < tiles; ++tile) {
-    const int64_t row = ((int64_t)blockIdx.x * tiles + tile) * kRowsPerBlock + wave * 32 + l32;
+    const int64_t row = row_first + (int64_t)tile * kRowsPerBlock;
     if ((int64_t)row - l32 >= n) return;   // the whole wavefront is past the end
     const bool live = row < n;
 
-    uint4 areg[kMaxF / 16];
+    uint4 areg[KS];
 #pragma unroll
-    for (int ks = 0; ks < kMaxF / 16; ++ks) {
-        areg[ks] = make_uint4(0u, 0u, 0u, 0u);
-        if (ks < ksteps && live) {
-            const int64_t at = row * kdim + ks * 16 + khalf * 8;
-            areg[ks] = *reinterpret_cast<const uint4*>(a_rows + at);
-            if (MASKED) areg[ks] = mask_vec(areg[ks], *reinterpret_cast<const uint4*>(mask_rows + at));
-        }
-    }
+    for (int ks = 0; ks < KS; ++ks) areg[ks] = MASKED ? mask_vec(nxt_a[ks], nxt_m[ks]) : nxt_a[ks];
+    if (tile + 1 < tiles) load_rows(row + kRowsPerBlock, nxt_a, nxt_m);
     f32x16 acc[4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 #pragma unroll
-    for (int ks = 0; ks < kMaxF / 16; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
         if (ks < ksteps) {
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
@@ -142,8 +160,8 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
                     if (RELU && !(v[i] > 0.0f)) v[i] = 0.0f;
                 }
                 uint2 q;
-                q.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-                q.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                q.x = pack_bf16(v[0], v[1]);
+                q.y = pack_bf16(v[2], v[3]);
                 const int col = n0 + nb * 32 + g4 * 8 + khalf * 4;
                 *reinterpret_cast<uint2*>(out + row * ndim + col) = q;
             }
@@ -185,21 +203,34 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
 
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r_end = r_begin + rows_per_block < n ? r_begin + rows_per_block : n;
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+    // this thread's pieces of one 32-row step: row r0 + lr, column chunks cq and cq + 8 of P and of dZ
+    // (dZ with its mask still beside it)
+    uint4 qp[2], qz[2], qh[MASKED ? 2 : 1];
+    auto load_step = [&](int64_t r0) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int cv = cq + half * 8;
             const int64_t r = r0 + lr;
-            uint4 qp = make_uint4(0u, 0u, 0u, 0u), qz = qp;
+            qp[half] = make_uint4(0u, 0u, 0u, 0u);
+            qz[half] = qp[half];
+            if (MASKED) qh[half] = qp[half];
             if (r < r_end) {
-                if (cv * 8 < cg) qp = *reinterpret_cast<const uint4*>(p + r * fin + c0 + cv * 8);
+                if (cv * 8 < cg) qp[half] = *reinterpret_cast<const uint4*>(p + r * fin + c0 + cv * 8);
                 if (cv * 8 < og) {
-                    qz = *reinterpret_cast<const uint4*>(gh + r * fout + o0 + cv * 8);
-                    if (MASKED) qz = mask_vec(qz, *reinterpret_cast<const uint4*>(h + r * fout + o0 + cv * 8));
+                    qz[half] = *reinterpret_cast<const uint4*>(gh + r * fout + o0 + cv * 8);
+                    if (MASKED) qh[half] = *reinterpret_cast<const uint4*>(h + r * fout + o0 + cv * 8);
                 }
             }
-            const uint32_t wp[4] = {qp.x, qp.y, qp.z, qp.w};
-            const uint32_t wz[4] = {qz.x, qz.y, qz.z, qz.w};
+        }
+    };
+    load_step(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int cv = cq + half * 8;
+            const uint4 z = MASKED ? mask_vec(qz[half], qh[half]) : qz[half];
+            const uint32_t wp[4] = {qp[half].x, qp[half].y, qp[half].z, qp[half].w};
+            const uint32_t wz[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 pt[(cv * 8 + 2 * j) * kTileLd + lr] = (uint16_t)(wp[j] & 0xffffu);
@@ -209,6 +240,7 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
             }
         }
         __syncthreads();
+        if (r0 + kTileRows < r_end) load_step(r0 + kTileRows);   // in flight while this step is multiplied
         if (wave_live) {
 #pragma unroll
             for (int ks = 0; ks < kTileRows / 16; ++ks) {
@@ -279,9 +311,18 @@ void launch_dense(const void* a, const void* mask, const void* w, void* out, int
     int64_t tiles = ceil_div(n, (int64_t)kRowsPerBlock * 512);   // keep at least ~512 workgroups
     tiles = tiles < 1 ? 1 : (tiles > 8 ? 8 : tiles);
     const dim3 grid((unsigned)ceil_div(n, kRowsPerBlock * tiles), (unsigned)ceil_div(ndim, ngroup));
-    dense_rows<MASKED, TRANS_W, RELU><<<grid, dim3(kThreads), 0, stream>>>(
-        static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
-        static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles);
+    if (kdim == 128 && ndim % 128 == 0)
+        dense_rows<MASKED, TRANS_W, RELU, 8, true><<<grid, dim3(kThreads), 0, stream>>>(
+            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
+            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles);
+    else if (kdim <= 128)
+        dense_rows<MASKED, TRANS_W, RELU, 8, false><<<grid, dim3(kThreads), 0, stream>>>(
+            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
+            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles);
+    else
+        dense_rows<MASKED, TRANS_W, RELU, kMaxF / 16, false><<<grid, dim3(kThreads), 0, stream>>>(
+            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
+            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles);
 }
 
 }  // namespace
