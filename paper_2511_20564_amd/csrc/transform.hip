@@ -23,7 +23,8 @@ constexpr int kRowsPerBlock = 32 * kWaves;   // one 32-row MFMA tile per wavefro
 constexpr int kMaxF = 256;
 constexpr int kPad = 8;                      // LDS row padding (elements) against bank conflicts
 constexpr int kWeightLds = 128 * (128 + kPad);  // elements; also fits 64 x (256 + kPad)
-constexpr int kTileRows = 32;                // node rows per step of the dW kernel
+constexpr int kTileRows = 64;                // node rows per step of the dW kernel
+constexpr int kRowPasses = kTileRows / 32;   // a thread stages one row of every 32
 constexpr int kTileLd = kTileRows + 8;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -205,12 +206,12 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     const int64_t r_end = r_begin + rows_per_block < n ? r_begin + rows_per_block : n;
     // this thread's pieces of one 32-row step: row r0 + lr, column chunks cq and cq + 8 of P and of dZ
     // (dZ with its mask still beside it)
-    uint4 qp[2], qz[2], qh[MASKED ? 2 : 1];
+    uint4 qp[2 * kRowPasses], qz[2 * kRowPasses], qh[MASKED ? 2 * kRowPasses : 1];
     auto load_step = [&](int64_t r0) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int cv = cq + half * 8;
-            const int64_t r = r0 + lr;
+        for (int half = 0; half < 2 * kRowPasses; ++half) {
+            const int cv = cq + (half & 1) * 8;
+            const int64_t r = r0 + lr + (half >> 1) * 32;
             qp[half] = make_uint4(0u, 0u, 0u, 0u);
             qz[half] = qp[half];
             if (MASKED) qh[half] = qp[half];
@@ -226,17 +227,18 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     load_step(r_begin);
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int cv = cq + half * 8;
+        for (int half = 0; half < 2 * kRowPasses; ++half) {
+            const int cv = cq + (half & 1) * 8;
+            const int tr = lr + (half >> 1) * 32;   // tile row
             const uint4 z = MASKED ? mask_vec(qz[half], qh[half]) : qz[half];
             const uint32_t wp[4] = {qp[half].x, qp[half].y, qp[half].z, qp[half].w};
             const uint32_t wz[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                pt[(cv * 8 + 2 * j) * kTileLd + lr] = (uint16_t)(wp[j] & 0xffffu);
-                pt[(cv * 8 + 2 * j + 1) * kTileLd + lr] = (uint16_t)(wp[j] >> 16);
-                zt[(cv * 8 + 2 * j) * kTileLd + lr] = (uint16_t)(wz[j] & 0xffffu);
-                zt[(cv * 8 + 2 * j + 1) * kTileLd + lr] = (uint16_t)(wz[j] >> 16);
+                pt[(cv * 8 + 2 * j) * kTileLd + tr] = (uint16_t)(wp[j] & 0xffffu);
+                pt[(cv * 8 + 2 * j + 1) * kTileLd + tr] = (uint16_t)(wp[j] >> 16);
+                zt[(cv * 8 + 2 * j) * kTileLd + tr] = (uint16_t)(wz[j] & 0xffffu);
+                zt[(cv * 8 + 2 * j + 1) * kTileLd + tr] = (uint16_t)(wz[j] >> 16);
             }
         }
         __syncthreads();
