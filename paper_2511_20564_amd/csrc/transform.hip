@@ -75,6 +75,28 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     const int ldb = kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
     const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int khalf = lane >> 5;
+    const int ksteps = EXACT ? KS : kdim / 16;
+    const int nblocks = EXACT ? 4 : ng / 32;
+    // rows of one tile as this lane feeds them to the matrix core (zeros past the end)
+    auto load_rows = [&](int64_t r, uint4 (&va)[KS], uint4 (&vm)[MASKED ? KS : 1]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            va[ks] = make_uint4(0u, 0u, 0u, 0u);
+            if (MASKED) vm[ks] = make_uint4(0u, 0u, 0u, 0u);
+            if (ks < ksteps && r < n) {
+                const int64_t at = r * kdim + ks * 16 + khalf * 8;
+                va[ks] = *reinterpret_cast<const uint4*>(a_rows + at);
+                if (MASKED) vm[ks] = *reinterpret_cast<const uint4*>(mask_rows + at);
+            }
+        }
+    };
+    const int64_t row_first = (int64_t)blockIdx.x * tiles * kRowsPerBlock + wave * 32 + l32;
+    uint4 nxt_a[KS], nxt_m[MASKED ? KS : 1];
+    load_rows(row_first, nxt_a, nxt_m);   // in flight while the weight tile is staged
     // stage the weight tile, k contiguous per output column.  Transposing: consecutive lanes take
     // consecutive k, so that their 2-byte LDS writes fall into consecutive banks.
     if (TRANS_W) {
@@ -99,28 +121,6 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     }
     __syncthreads();
 
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int l32 = lane & 31;
-    const int khalf = lane >> 5;
-    const int ksteps = EXACT ? KS : kdim / 16;
-    const int nblocks = EXACT ? 4 : ng / 32;
-    // rows of one tile as this lane feeds them to the matrix core (zeros past the end)
-    auto load_rows = [&](int64_t r, uint4 (&va)[KS], uint4 (&vm)[MASKED ? KS : 1]) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            va[ks] = make_uint4(0u, 0u, 0u, 0u);
-            if (MASKED) vm[ks] = make_uint4(0u, 0u, 0u, 0u);
-            if (ks < ksteps && r < n) {
-                const int64_t at = r * kdim + ks * 16 + khalf * 8;
-                va[ks] = *reinterpret_cast<const uint4*>(a_rows + at);
-                if (MASKED) vm[ks] = *reinterpret_cast<const uint4*>(mask_rows + at);
-            }
-        }
-    };
-    const int64_t row_first = (int64_t)blockIdx.x * tiles * kRowsPerBlock + wave * 32 + l32;
-    uint4 nxt_a[KS], nxt_m[MASKED ? KS : 1];
-    load_rows(row_first, nxt_a, nxt_m);
 #pragma unroll 1
     for (int tile = 0; tile < tiles; ++tile) {
     const int64_t row = row_first + (int64_t)tile * kRowsPerBlock;
