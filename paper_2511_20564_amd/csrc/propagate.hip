@@ -470,19 +470,22 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
 }
 
 constexpr int kReduceThreads = 256;
+constexpr int kReduceBlocks = 8192;   // at most this many workgroups; they stride over the split rows
 
-// Rows cut into segments: add their partial sums in a fixed order.  One workgroup per long row;
-// thread (sl, cv) sums slots sl, sl+SL, ... of column quad cv in double, then the SL lane sums
-// are added in lane order.
+// Rows cut into segments: add their partial sums in a fixed order.  One workgroup per long row
+// (the launch is sized for an upper bound of such rows that depends on nnz only, capped, and
+// the workgroups stride over the real ones); thread (sl, cv) sums slots sl, sl+SL, ... of column
+// quad cv in double, then the SL lane sums are added in lane order.
 template <typename T>
 __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerArgs<T> a) {
     constexpr int kThreads = kReduceThreads;
     __shared__ double red[kThreads][4];
-    if ((int32_t)blockIdx.x >= a.sched.header->n_multi) return;
-    const int32_t k = a.sched.multi_row[blockIdx.x];  // internal row
+    const int32_t n_multi = a.sched.header->n_multi;
+    for (int32_t m = blockIdx.x; m < n_multi; m += gridDim.x) {
+    const int32_t k = a.sched.multi_row[m];  // internal row
     const int32_t node = a.sched.orig[k];
-    const int32_t base = a.sched.slot_base[blockIdx.x];
-    const int32_t cnt = a.sched.slot_cnt[blockIdx.x];
+    const int32_t base = a.sched.slot_base[m];
+    const int32_t cnt = a.sched.slot_cnt[m];
     const float s = a.dinv_sqrt[node];
     const int quads = a.F / 4;
     for (int q0 = 0; q0 < quads; q0 += kThreads) {
@@ -493,18 +496,9 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
         double sum[4] = {0.0, 0.0, 0.0, 0.0};
         if (sl < lanes) {
             const float* p = a.partial + (int64_t)base * a.F + (int64_t)(q0 + cv) * 4;
-            int32_t q = sl;
-            for (; q + 3 * lanes < cnt; q += 4 * lanes) {
-                const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * a.F);
-                const float4 v1 = *reinterpret_cast<const float4*>(p + (int64_t)(q + lanes) * a.F);
-                const float4 v2 = *reinterpret_cast<const float4*>(p + (int64_t)(q + 2 * lanes) * a.F);
-                const float4 v3 = *reinterpret_cast<const float4*>(p + (int64_t)(q + 3 * lanes) * a.F);
-                sum[0] += (double)v0.x; sum[1] += (double)v0.y; sum[2] += (double)v0.z; sum[3] += (double)v0.w;
-                sum[0] += (double)v1.x; sum[1] += (double)v1.y; sum[2] += (double)v1.z; sum[3] += (double)v1.w;
-                sum[0] += (double)v2.x; sum[1] += (double)v2.y; sum[2] += (double)v2.z; sum[3] += (double)v2.w;
-                sum[0] += (double)v3.x; sum[1] += (double)v3.y; sum[2] += (double)v3.z; sum[3] += (double)v3.w;
-            }
-            for (; q < cnt; q += lanes) {
+            // slots sl, sl + lanes, ... in that order; unrolled so that eight loads are in flight
+#pragma unroll 8
+            for (int32_t q = sl; q < cnt; q += lanes) {
                 const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * a.F);
                 sum[0] += (double)v0.x; sum[1] += (double)v0.y; sum[2] += (double)v0.z; sum[3] += (double)v0.w;
             }
@@ -527,6 +521,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
             }
         }
         __syncthreads();
+    }
     }
 }
 
@@ -620,7 +615,8 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     profile_mark(stream, true);
     E2EG_LAUNCH_CHECK("spmm_rows");
     if (nnz > kSegLen) {  // otherwise no row has several segments
-        reduce_split_rows<T><<<dim3((unsigned)sched_max_multi(nnz)), dim3(kReduceThreads), 0, stream>>>(a);
+        const int64_t blocks = sched_max_multi(nnz) < kReduceBlocks ? sched_max_multi(nnz) : kReduceBlocks;
+        reduce_split_rows<T><<<dim3((unsigned)blocks), dim3(kReduceThreads), 0, stream>>>(a);
         E2EG_LAUNCH_CHECK("reduce_split_rows");
     }
     return E2EG_OK;
