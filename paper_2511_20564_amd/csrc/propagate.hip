@@ -375,6 +375,7 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
 constexpr int kShortPerWave = 8;   // short rows a wavefront works through, 64/G at a time
+constexpr int kSegBlocksPerXcd = 2048;    // most A-workgroups per XCD
 constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when the graph cannot have that many such rows)
 
 // Three kinds of workgroup.
@@ -598,7 +599,9 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const uint64_t table_bytes = (uint64_t)(n + 1) * row_bytes;
     const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
     // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs
-    const int64_t a_blocks = nnz > kSegLen ? ceil_div(ceil_div(sched_max_slot(n, nnz), kWaves), kXcds) + 1 : 0;
+    // (capped: the A-workgroups go round their stretch again, and unused workgroups still cost a dispatch)
+    int64_t a_blocks = nnz > kSegLen ? ceil_div(ceil_div(sched_max_slot(n, nnz), kWaves), kXcds) + 1 : 0;
+    if (a_blocks > kSegBlocksPerXcd) a_blocks = kSegBlocksPerXcd;
     int64_t b_blocks = nnz > kShortMax ? ceil_div(ceil_div(sched_max_plain(nnz), kWaves), kXcds) + 1 : 0;
     if (b_blocks > kSingleBlocksPerXcd) b_blocks = kSingleBlocksPerXcd;
     const int64_t c_blocks = ceil_div(ceil_div(n, kWaves * kShortPerWave), kXcds) + 1;
