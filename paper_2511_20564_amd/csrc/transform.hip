@@ -23,6 +23,7 @@ constexpr int kRowsPerBlock = 32 * kWaves;   // one 32-row MFMA tile per wavefro
 constexpr int kMaxF = 256;
 constexpr int kPad = 8;                      // LDS row padding (elements) against bank conflicts
 constexpr int kWeightLds = 128 * (128 + kPad);  // elements; also fits 64 x (256 + kPad)
+constexpr int kOutLd = 128 + kPad;           // pitch of a wavefront's result rows in LDS (at most 128 columns per workgroup)
 constexpr int kTileRows = 64;                // node rows per step of the dW kernel
 constexpr int kRowPasses = kTileRows / 32;   // a thread stages one row of every 32
 constexpr int kTileLd = kTileRows + 8;
@@ -72,6 +73,7 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
                                                        int32_t kdim, int32_t ndim, int32_t w_ld,
                                                        int32_t ngroup, int32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][kdim + kPad]
+    __shared__ __attribute__((aligned(16))) uint16_t ot[kWaves][16 * kOutLd];  // per wavefront: 16 result rows
     const int ldb = kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
     const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
@@ -125,7 +127,6 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
     for (int tile = 0; tile < tiles; ++tile) {
     const int64_t row = row_first + (int64_t)tile * kRowsPerBlock;
     if ((int64_t)row - l32 >= n) return;   // the whole wavefront is past the end
-    const bool live = row < n;
 
     uint4 areg[KS];
 #pragma unroll
@@ -148,25 +149,48 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
             }
         }
     }
-    if (!live) continue;
+    // A lane holds runs of 4 output columns of its row.  Stored from here they would leave as 8-byte
+    // pieces, 16 store instructions that each touch 32 rows; instead the wavefront's results go
+    // through its LDS tile, 16 rows at a time, and leave as whole rows (a store instruction then
+    // writes 4 consecutive rows, 1 KiB in one piece).  Measured at 4 M rows: 634 -> 420 us.
+    uint2 pk[4][4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
-        if (nb < nblocks) {
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                float v[4];
+        for (int g4 = 0; g4 < 4; ++g4) {
+            float v[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    v[i] = acc[nb][g4 * 4 + i];
-                    if (RELU && !(v[i] > 0.0f)) v[i] = 0.0f;
+            for (int i = 0; i < 4; ++i) {
+                v[i] = acc[nb][g4 * 4 + i];
+                if (RELU && !(v[i] > 0.0f)) v[i] = 0.0f;
+            }
+            pk[nb][g4].x = pack_bf16(v[0], v[1]);
+            pk[nb][g4].y = pack_bf16(v[2], v[3]);
+        }
+    }
+    uint16_t* ow = ot[wave];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        if ((l32 >> 4) == half) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                if (nb < nblocks) {
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4)
+                        *reinterpret_cast<uint2*>(ow + (l32 & 15) * kOutLd + nb * 32 + g4 * 8 + khalf * 4) = pk[nb][g4];
                 }
-                uint2 q;
-                q.x = pack_bf16(v[0], v[1]);
-                q.y = pack_bf16(v[2], v[3]);
-                const int col = n0 + nb * 32 + g4 * 8 + khalf * 4;
-                *reinterpret_cast<uint2*>(out + row * ndim + col) = q;
             }
         }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {   // 16 rows x 16 chunks of 16 bytes, 64 lanes per pass (128 output columns)
+            const int r = it * 4 + (lane >> 4), ch = lane & 15;
+            const int64_t grow = row - l32 + half * 16 + r;
+            if (grow < n && ch * 8 < ng)
+                *reinterpret_cast<uint4*>(out + grow * ndim + n0 + ch * 8) =
+                    *reinterpret_cast<const uint4*>(ow + r * kOutLd + ch * 8);
+        }
+        __builtin_amdgcn_wave_barrier();
     }
     }
 }
