@@ -263,17 +263,33 @@ __global__ void place_short_rows(const uint64_t* __restrict__ keys, int64_t n, S
 }
 
 // One thread per CSR entry e: key = (internal row << bits) | internal column.
-__global__ void entry_keys(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                           const int32_t* __restrict__ zpos, int64_t n, int64_t nnz, int bits,
-                           uint64_t* __restrict__ keys) {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= nnz) return;
-    int64_t lo = 0, hi = n - 1;  // last i with row_ptr[i] <= e
+// The row of entry e: the last i in [lo, hi] with row_ptr[i] <= e.
+__device__ __forceinline__ int64_t row_of_entry(const int32_t* __restrict__ row_ptr, int64_t e, int64_t lo, int64_t hi) {
     while (lo < hi) {
         const int64_t mid = (lo + hi + 1) >> 1;
         if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
     }
-    keys[e] = ((uint64_t)(uint32_t)zpos[lo] << bits) | (uint32_t)zpos[col_idx[e]];
+    return lo;
+}
+
+// A workgroup's entries are consecutive, so their rows lie between the rows of its first and of
+// its last entry: two threads search all rows for those, the others then search that short range.
+__global__ __launch_bounds__(kThreads) void entry_keys(const int32_t* __restrict__ row_ptr,
+                                                       const int32_t* __restrict__ col_idx,
+                                                       const int32_t* __restrict__ zpos, int64_t n, int64_t nnz,
+                                                       int bits, uint64_t* __restrict__ keys) {
+    __shared__ int64_t range[2];
+    const int64_t first = (int64_t)blockIdx.x * kThreads;
+    const int64_t e = first + threadIdx.x;
+    if (threadIdx.x == 0) range[0] = row_of_entry(row_ptr, first, 0, n - 1);
+    if (threadIdx.x == 64) {
+        const int64_t last = first + kThreads - 1 < nnz ? first + kThreads - 1 : nnz - 1;
+        range[1] = row_of_entry(row_ptr, last, 0, n - 1);
+    }
+    __syncthreads();
+    if (e >= nnz) return;
+    const int64_t row = row_of_entry(row_ptr, e, range[0], range[1]);
+    keys[e] = ((uint64_t)(uint32_t)zpos[row] << bits) | (uint32_t)zpos[col_idx[e]];
 }
 
 __global__ void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, int bits,
@@ -303,15 +319,21 @@ __global__ __launch_bounds__(kThreads) void weighted_degrees(const int32_t* __re
 
 // One thread per stored entry e of the caller's CSR: its value goes to the place of the same entry
 // in the internal CSR (row zpos[i], column zpos[j], found by binary search in that row).
-__global__ void place_values(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                             const float* __restrict__ val, int64_t n, int64_t nnz, SchedView s) {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= nnz) return;
-    int64_t lo = 0, hi = n - 1;  // last i with row_ptr[i] <= e
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) >> 1;
-        if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
+__global__ __launch_bounds__(kThreads) void place_values(const int32_t* __restrict__ row_ptr,
+                                                         const int32_t* __restrict__ col_idx,
+                                                         const float* __restrict__ val, int64_t n, int64_t nnz,
+                                                         SchedView s) {
+    __shared__ int64_t range[2];   // rows of the workgroup's first and last entry (see entry_keys)
+    const int64_t first = (int64_t)blockIdx.x * kThreads;
+    const int64_t e = first + threadIdx.x;
+    if (threadIdx.x == 0) range[0] = row_of_entry(row_ptr, first, 0, n - 1);
+    if (threadIdx.x == 64) {
+        const int64_t last = first + kThreads - 1 < nnz ? first + kThreads - 1 : nnz - 1;
+        range[1] = row_of_entry(row_ptr, last, 0, n - 1);
     }
+    __syncthreads();
+    if (e >= nnz) return;
+    const int64_t lo = row_of_entry(row_ptr, e, range[0], range[1]);
     const int32_t p = s.zpos[lo];
     const int32_t c = s.zpos[col_idx[e]];
     int32_t a = s.zrow_ptr[p], b = s.zrow_ptr[p + 1];   // first position with zcol >= c

@@ -35,7 +35,9 @@ __global__ __launch_bounds__(kThreads) void sort_histogram(const uint64_t* __res
 
 // Stable scatter.  A block's tile is split into one contiguous chunk per wavefront; a wavefront
 // walks its chunk 64 keys at a time, ranking equal digits by lane order plus a running
-// per-wavefront digit count, so ranks follow input order.
+// per-wavefront digit count, so ranks follow input order.  The keys are then put in digit order
+// inside the tile (in LDS) and written out from there, consecutive threads writing consecutive
+// keys: keys of one digit leave as one contiguous run instead of as single 8-byte stores.
 // `offs` is the digit-major table [256][nblocks] of scanned offsets, or, with COUNTS, the raw
 // block-major histogram [nblocks][256], from which every workgroup then adds up its own 256
 // offsets (few blocks: a short loop of coalesced reads that saves the launches of a scan).
@@ -45,14 +47,18 @@ __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restr
                                                          int64_t count, int shift,
                                                          const int32_t* __restrict__ offs,
                                                          int32_t nblocks) {
-    __shared__ int wave_cnt[kWaves][256];
+    __shared__ int wave_cnt[kWaves][256];   // keys of digit d in wavefront w, then their first place in the tile
     __shared__ int wave_tot[kWaves];
+    __shared__ int tile_first[256];         // first place of digit d in the tile
+    __shared__ int global_first[256];       // where the tile's keys of digit d go
+    __shared__ uint64_t tile[kSortTile];
     for (int k = threadIdx.x; k < kWaves * 256; k += kThreads) (&wave_cnt[0][0])[k] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const int64_t chunk = (int64_t)blockIdx.x * kSortTile + (int64_t)wave * (64 * kSortItems);
+    const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+    const int64_t chunk = tile_base + (int64_t)wave * (64 * kSortItems);
     uint64_t key[kSortItems];
     int rank[kSortItems];
 #pragma unroll
@@ -74,18 +80,14 @@ __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restr
         if (valid && below == 0) wave_cnt[wave][d] = pre + __popcll(peers);
     }
     __syncthreads();
-    int base;
-    if (COUNTS) {
-        // keys with a smaller digit anywhere, plus keys with this digit in earlier blocks
-        int before = 0, total = 0;
-        const int32_t* col = offs + threadIdx.x;
-#pragma unroll 16
-        for (int b = 0; b < nblocks; ++b) {
-            const int c = col[(int64_t)b * 256];
-            if (b < (int)blockIdx.x) before += c;
-            total += c;
-        }
-        int inc = total;  // inclusive scan over the 256 digits: within the wavefront, then across the four
+    {
+        // thread d: this tile's keys of digit d (all wavefronts), their first place in the tile
+        // (exclusive scan over the digits), and where they go
+        const int d = threadIdx.x;
+        int mine = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) mine += wave_cnt[w][d];
+        int inc = mine;
 #pragma unroll
         for (int dlt = 1; dlt < 64; dlt <<= 1) {
             const int t = __shfl_up(inc, dlt, 64);
@@ -93,21 +95,46 @@ __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restr
         }
         if (lane == 63) wave_tot[wave] = inc;
         __syncthreads();
-        int lower = 0;
+        int first = inc - mine;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w)
-            if (w < wave) lower += wave_tot[w];
-        base = lower + inc - total + before;
-    } else {
-        base = offs[(int64_t)threadIdx.x * nblocks + blockIdx.x];
-    }
-    {
-        const int d = threadIdx.x;
+            if (w < wave) first += wave_tot[w];
+        tile_first[d] = first;
+        int base;
+        if (COUNTS) {
+            // keys with a smaller digit anywhere, plus keys with this digit in earlier blocks
+            int before = 0, total = 0;
+            const int32_t* col = offs + d;
+#pragma unroll 16
+            for (int b = 0; b < nblocks; ++b) {
+                const int c = col[(int64_t)b * 256];
+                if (b < (int)blockIdx.x) before += c;
+                total += c;
+            }
+            __syncthreads();   // wave_tot is reused
+            int ginc = total;
+#pragma unroll
+            for (int dlt = 1; dlt < 64; dlt <<= 1) {
+                const int t = __shfl_up(ginc, dlt, 64);
+                if (lane >= dlt) ginc += t;
+            }
+            if (lane == 63) wave_tot[wave] = ginc;
+            __syncthreads();
+            int lower = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+                if (w < wave) lower += wave_tot[w];
+            base = lower + ginc - total + before;
+        } else {
+            base = offs[(int64_t)d * nblocks + blockIdx.x];
+        }
+        global_first[d] = base;
+        int at = first;   // wave_cnt[w][d] becomes the first tile place of wavefront w's keys of digit d
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            int c = wave_cnt[w][d];
-            wave_cnt[w][d] = base;
-            base += c;
+            const int c = wave_cnt[w][d];
+            wave_cnt[w][d] = at;
+            at += c;
         }
     }
     __syncthreads();
@@ -116,8 +143,16 @@ __global__ __launch_bounds__(kThreads) void sort_scatter(const uint64_t* __restr
         const int64_t idx = chunk + r * 64 + lane;
         if (idx < count) {
             const int d = (int)((key[r] >> shift) & 255);
-            out[(int64_t)wave_cnt[wave][d] + rank[r]] = key[r];
+            tile[wave_cnt[wave][d] + rank[r]] = key[r];
         }
+    }
+    __syncthreads();
+    const int64_t left = count - tile_base;
+    const int valid_keys = left < kSortTile ? (int)left : kSortTile;
+    for (int p = threadIdx.x; p < valid_keys; p += kThreads) {
+        const uint64_t k = tile[p];
+        const int d = (int)((k >> shift) & 255);
+        out[(int64_t)global_first[d] + (p - tile_first[d])] = k;
     }
 }
 
