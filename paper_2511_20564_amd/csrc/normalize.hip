@@ -27,6 +27,7 @@ namespace e2eg {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kLengthCutCost = 6;   // in quarters: an entry of a segment cut by length only weighs 1.5 entries in the deal
 
 // Per node: degree, d^-1/2, and the sort key (larger degree first, then node id): n - d in the
 // upper half, which needs bits_for(n + 1) bits, so small graphs sort in few passes.
@@ -230,15 +231,21 @@ __global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
 }
 
 // Sorted keys -> the ordered segment list, and each slotted segment's length for the deal.
+// (A segment cut by length only reaches across many windows and mostly misses in L2, so its
+// entries count kLengthCutCost / 4 times in the deal; such segments have the lowest first columns
+// and would otherwise make the first XCD's stretch the slowest.)
 __global__ void place_segments(const uint64_t* __restrict__ keys, const Segment* __restrict__ seg_tmp,
-                               SchedView s, int32_t* __restrict__ seg_len) {
+                               SchedView s, int32_t wide_rows, int32_t wide_min, int32_t* __restrict__ seg_len) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > s.max_seg) return;
     int32_t len = 0;
     if (p < s.header->n_seg) {
         const Segment g = seg_tmp[(uint32_t)keys[p]];
         s.segs[p] = g;
-        if (p < s.header->n_slot) len = g.end - g.beg;
+        if (p < s.header->n_slot) {
+            const bool wide = g.row < wide_rows && s.zrow_ptr[g.row + 1] - s.zrow_ptr[g.row] >= wide_min;
+            len = wide ? g.end - g.beg : (g.end - g.beg) * kLengthCutCost / 4;
+        }
     }
     seg_len[p] = len;
 }
@@ -514,7 +521,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         }
         int32_t st = radix_sort_u64(&src, &dst, view.max_seg, 32, bits + 2 < 32 ? bits + 2 : 32, w.sort_ws, stream);
         if (st != E2EG_OK) return st;
-        place_segments<<<grid_for(view.max_seg + 1), blk, 0, stream>>>(src, w.seg_tmp, view, w.seg_len);
+        place_segments<<<grid_for(view.max_seg + 1), blk, 0, stream>>>(src, w.seg_tmp, view, wide_rows, wide_min, w.seg_len);
         E2EG_LAUNCH_CHECK("place_segments");
         E2EG_HIP_TRY(exclusive_scan_i32(w.seg_len, w.seg_len, view.max_seg + 1, nullptr, w.scan_ws, stream));
         deal_segments<<<grid_for(view.max_slot + 1), blk, 0, stream>>>(w.seg_len, view);
