@@ -6,19 +6,25 @@ import pytest
 import torch
 
 from parity import to_device
-from workloads import make_config
+from workloads import make_config, make_edge_weights
 
 pytestmark = pytest.mark.gpu
 
 
-def test_propagate_fwd_bwd_replayed_from_a_graph():
+@pytest.mark.parametrize("weighted", [False, True])
+def test_propagate_fwd_bwd_replayed_from_a_graph(weighted):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import paper_2511_20564_amd.device as dev
     dev.B.load_library()
     c = make_config(2, scale=0.2)
     K, dt, F = c["K"], c["dtype"], c["F"]
-    g = dev.build_graph(c["n_users"], c["n_items"], torch.from_numpy(c["users"]).cuda(), torch.from_numpy(c["items"]).cuda())
+    u, i = torch.from_numpy(c["users"]).cuda(), torch.from_numpy(c["items"]).cuda()
+    if weighted:
+        g = dev.build_weighted_graph(c["n_users"], c["n_items"], u, i,
+                                     torch.from_numpy(make_edge_weights(c["users"].size, seed=1)).cuda())
+    else:
+        g = dev.build_graph(c["n_users"], c["n_items"], u, i)
     X0, gY = to_device(c["X0"], dt), to_device(c["gY"], dt)
     ws = dev.propagate_workspace(g, X0.dtype, F, K)
     out_f, out_b = torch.empty_like(X0), torch.empty_like(X0)
