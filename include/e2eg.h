@@ -291,7 +291,8 @@ int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row
  * become integers, floor(p / pmax * 2^24) with pmax the row's largest usable weight, decided in fp32
  * with IEEE rounding, at least 1 where p > 0; the diagonal entry and entries that are not positive
  * and finite get 0 and are never drawn.  d_table (e2eg_sampler_table_bytes(nnz), 256-byte aligned)
- * receives their running sums over the whole CSR (nnz + 1 values of 64 bits).
+ * receives their running sums over the whole CSR (nnz + 1 values of 64 bits).  The workspace
+ * (e2eg_sampler_prepare_workspace_bytes(n, nnz)) holds the row maxima and the scan's partial sums.
  *
  * e2eg_sample_subgraph: hop h = 0..L-1 expands its frontier (hop 0: the distinct seeds; hop h+1:
  * the nodes first reached at hop h), each frontier node u with fan-out k = h_fanout[h] (HOST array):
@@ -312,7 +313,7 @@ int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row
  */
 int32_t e2eg_sampling_weights(int64_t nnz, const float* d_val, float beta, float* d_p, void* stream);
 size_t e2eg_sampler_table_bytes(int64_t nnz);
-size_t e2eg_sampler_prepare_workspace_bytes(int64_t nnz);
+size_t e2eg_sampler_prepare_workspace_bytes(int32_t n, int64_t nnz);
 int32_t e2eg_sampler_prepare(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                              const float* d_p, void* d_table, size_t table_bytes, void* ws, size_t ws_bytes,
                              void* stream);

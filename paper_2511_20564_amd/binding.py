@@ -59,7 +59,7 @@ SIGNATURES = {
     "e2eg_propagate_weighted_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_sampling_weights": (_i32, [_i64, _vp, ctypes.c_float, _vp, _vp]),
     "e2eg_sampler_table_bytes": (_sz, [_i64]),
-    "e2eg_sampler_prepare_workspace_bytes": (_sz, [_i64]),
+    "e2eg_sampler_prepare_workspace_bytes": (_sz, [_i32, _i64]),
     "e2eg_sampler_prepare": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
     "e2eg_sample_capacity": (_i64, [_i32, _i32, _i32, ctypes.POINTER(_i32)]),
     "e2eg_sample_subgraph_workspace_bytes": (_sz, [_i32, _i32, _i32, ctypes.POINTER(_i32)]),
@@ -220,8 +220,8 @@ def e2eg_sampler_table_bytes(nnz) -> int:
     return int(load_library().e2eg_sampler_table_bytes(nnz))
 
 
-def e2eg_sampler_prepare_workspace_bytes(nnz) -> int:
-    return int(load_library().e2eg_sampler_prepare_workspace_bytes(nnz))
+def e2eg_sampler_prepare_workspace_bytes(n, nnz) -> int:
+    return int(load_library().e2eg_sampler_prepare_workspace_bytes(n, nnz))
 
 
 def e2eg_sampler_prepare(n, nnz, d_row_ptr, d_col_idx, d_p, d_table, table_bytes, ws, ws_bytes=None, stream=0):

@@ -7,6 +7,7 @@
 //   * e2eg_sampler_prepare turns each row's weights into integers (2^24 at the row maximum, the
 //     division decided in fp32 with IEEE rounding) and prefix-sums them over the whole CSR: the
 //     table holds cum[e] = sum of the integer weights before entry e, nnz + 1 values of 64 bits.
+//     One thread per entry throughout, so that a row of a million entries is no wavefront's loop.
 //   * a draw is one thread: 64 random bits from the counter-based generator Philox4x32-10 (Salmon,
 //     Moraes, Dror, Shaw, SC 2011; counter = (draw, node, hop, 0), key = the seed), scaled to the
 //     row total by a 64x64->128-bit multiply, then a binary search in the row's slice of the table.
@@ -37,31 +38,77 @@ __global__ void pow_weights(const float* __restrict__ val, int64_t nnz, float be
     p[e] = r;
 }
 
-// One wavefront per row: the largest usable weight off the diagonal, then the integer weights.
-__global__ __launch_bounds__(kThreads) void quantise_rows(const int32_t* __restrict__ row_ptr,
-                                                          const int32_t* __restrict__ col_idx,
-                                                          const float* __restrict__ p, int64_t n, int64_t nnz,
-                                                          uint64_t* __restrict__ q) {
+// The row of entry e: the last i in [lo, hi] with row_ptr[i] <= e.
+__device__ __forceinline__ int64_t row_of_entry(const int32_t* __restrict__ row_ptr, int64_t e, int64_t lo, int64_t hi) {
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Rows of a workgroup's (consecutive) entries: two threads search all rows for the first and the last
+// entry's, every thread then searches that short range.  -> the row of entry `e` (e < nnz).
+__device__ __forceinline__ int64_t row_in_block(const int32_t* __restrict__ row_ptr, int64_t n, int64_t nnz,
+                                                int64_t first, int64_t e, int64_t* range) {
+    if (threadIdx.x == 0) range[0] = row_of_entry(row_ptr, first, 0, n - 1);
+    if (threadIdx.x == 64) {
+        const int64_t last = first + kThreads - 1 < nnz ? first + kThreads - 1 : nnz - 1;
+        range[1] = row_of_entry(row_ptr, last, 0, n - 1);
+    }
+    __syncthreads();
+    return e < nnz ? row_of_entry(row_ptr, e, range[0], range[1]) : -1;
+}
+
+// One thread per entry: the largest usable weight off the diagonal of every row, as the bit pattern
+// of a positive float (which orders like an integer).  The entries of a row are neighbours, so a
+// wavefront first takes the maximum of each run of equal rows among its lanes and only the first
+// lane of a run goes to memory: a row of a million entries costs some ten thousand atomics.
+__global__ __launch_bounds__(kThreads) void row_max(const int32_t* __restrict__ row_ptr,
+                                                    const int32_t* __restrict__ col_idx, const float* __restrict__ p,
+                                                    int64_t n, int64_t nnz, int32_t* row_max_bits) {
+    __shared__ int64_t range[2];
+    const int64_t first = (int64_t)blockIdx.x * kThreads;
+    const int64_t e = first + threadIdx.x;
+    const int64_t row = row_in_block(row_ptr, n, nnz, first, e, range);
     const int lane = threadIdx.x & 63;
-    const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
-    if (row == 0 && lane == 0) q[nnz] = 0;  // the scan runs over nnz + 1 values
-    if (row >= n) return;
-    const int32_t beg = row_ptr[row], end = row_ptr[row + 1];
-    float pmax = 0.0f;
-    for (int32_t e = beg + lane; e < end; e += 64) {
+    int32_t bits = 0;
+    if (row >= 0) {
         const float v = p[e];
-        if (col_idx[e] != (int32_t)row && usable(v) && v > pmax) pmax = v;
+        if (col_idx[e] != (int32_t)row && usable(v)) bits = __float_as_int(v);
     }
-    for (int off = 32; off > 0; off >>= 1) pmax = fmaxf(pmax, __shfl_xor(pmax, off));
-    for (int32_t e = beg + lane; e < end; e += 64) {
-        const float v = p[e];
-        uint64_t w = 0;
-        if (col_idx[e] != (int32_t)row && usable(v)) {
-            const float scaled = floorf(__fmul_rn(__fdiv_rn(v, pmax), 16777216.0f));
-            w = scaled >= 1.0f ? (uint64_t)scaled : 1u;
-        }
-        q[e] = w;
+    const int32_t r32 = (int32_t)row;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int32_t other = __shfl_down(bits, d, 64);
+        const int32_t other_row = __shfl_down(r32, d, 64);
+        if (lane + d < 64 && other_row == r32 && other > bits) bits = other;
     }
+    const int32_t before = __shfl_up(r32, 1, 64);
+    if (row >= 0 && (lane == 0 || before != r32) && bits > 0) atomicMax(row_max_bits + row, bits);
+}
+
+// One thread per entry: its integer weight.  The entry past the end gets the 0 that closes the scan.
+__global__ __launch_bounds__(kThreads) void quantise_entries(const int32_t* __restrict__ row_ptr,
+                                                             const int32_t* __restrict__ col_idx,
+                                                             const float* __restrict__ p, int64_t n, int64_t nnz,
+                                                             const int32_t* __restrict__ row_max_bits,
+                                                             uint64_t* __restrict__ q) {
+    __shared__ int64_t range[2];
+    const int64_t first = (int64_t)blockIdx.x * kThreads;
+    const int64_t e = first + threadIdx.x;
+    if (e == nnz) q[nnz] = 0;
+    if (first >= nnz) return;   // the whole workgroup (only the one that holds entry nnz alone)
+    const int64_t row = row_in_block(row_ptr, n, nnz, first, e, range);
+    if (row < 0) return;
+    const float v = p[e];
+    uint64_t w = 0;
+    if (col_idx[e] != (int32_t)row && usable(v)) {
+        const float pmax = __int_as_float(row_max_bits[row]);
+        const float scaled = floorf(__fmul_rn(__fdiv_rn(v, pmax), 16777216.0f));
+        w = scaled >= 1.0f ? (uint64_t)scaled : 1u;
+    }
+    q[e] = w;
 }
 
 __global__ void fill_i32(int32_t* __restrict__ p, int64_t count, int32_t v) {
@@ -283,9 +330,9 @@ extern "C" size_t e2eg_sampler_table_bytes(int64_t nnz) {
     return align_up((size_t)(nnz + 1) * sizeof(uint64_t));
 }
 
-extern "C" size_t e2eg_sampler_prepare_workspace_bytes(int64_t nnz) {
-    if (nnz < 0) return 0;
-    return scan_u64_workspace_bytes(nnz + 1);
+extern "C" size_t e2eg_sampler_prepare_workspace_bytes(int32_t n, int64_t nnz) {
+    if (n < 0 || nnz < 0) return 0;
+    return align_up((size_t)(n > 0 ? n : 1) * sizeof(int32_t)) + scan_u64_workspace_bytes(nnz + 1);   // row maxima, scan
 }
 
 extern "C" int32_t e2eg_sampler_prepare(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
@@ -300,16 +347,25 @@ extern "C" int32_t e2eg_sampler_prepare(int32_t n, int64_t nnz, const int32_t* d
     if (!aligned_to(d_table, kAlign) || table_bytes < e2eg_sampler_table_bytes(nnz))
         return fail(E2EG_ERR_CAPACITY, "sampler_prepare: d_table needs %zu bytes, 256-byte aligned",
                     e2eg_sampler_table_bytes(nnz));
-    const size_t need = e2eg_sampler_prepare_workspace_bytes(nnz);
+    const size_t need = e2eg_sampler_prepare_workspace_bytes(n, nnz);
     if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
         return fail(E2EG_ERR_WORKSPACE, "sampler_prepare: workspace needs %zu bytes, 256-byte aligned", need);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     uint64_t* q = static_cast<uint64_t*>(d_table);
-    // at least one wavefront runs, which also writes the closing zero
-    quantise_rows<<<grid_for(((int64_t)n > 0 ? (int64_t)n : 1) * 64), dim3(kThreads), 0, stream>>>(d_row_ptr, d_col_idx, d_p,
-                                                                                                 n, nnz, q);
-    E2EG_LAUNCH_CHECK("quantise_rows");
-    E2EG_HIP_TRY(exclusive_scan_u64(q, q, nnz + 1, nullptr, ws, stream));
+    int32_t* row_max_bits = static_cast<int32_t*>(ws);
+    void* scan_ws = static_cast<char*>(ws) + align_up((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+    const dim3 blk(kThreads);
+    if (n > 0) {
+        fill_i32<<<grid_for(n), blk, 0, stream>>>(row_max_bits, n, 0);
+        E2EG_LAUNCH_CHECK("fill_i32");
+    }
+    if (nnz > 0) {
+        row_max<<<grid_for(nnz), blk, 0, stream>>>(d_row_ptr, d_col_idx, d_p, n, nnz, row_max_bits);
+        E2EG_LAUNCH_CHECK("row_max");
+    }
+    quantise_entries<<<grid_for(nnz + 1), blk, 0, stream>>>(d_row_ptr, d_col_idx, d_p, n, nnz, row_max_bits, q);
+    E2EG_LAUNCH_CHECK("quantise_entries");
+    E2EG_HIP_TRY(exclusive_scan_u64(q, q, nnz + 1, nullptr, scan_ws, stream));
     return E2EG_OK;
 }
 

@@ -131,7 +131,7 @@ def sampler_table(g: Graph, beta: float = 1.0, p: torch.Tensor | None = None) ->
         B.e2eg_sampling_weights(g.nnz, g.val, float(beta), p, _stream())
     assert p.dtype == torch.float32 and p.is_contiguous() and p.numel() >= g.nnz
     table = _bytes(B.e2eg_sampler_table_bytes(g.nnz), dev)
-    ws = _bytes(B.e2eg_sampler_prepare_workspace_bytes(g.nnz), dev)
+    ws = _bytes(B.e2eg_sampler_prepare_workspace_bytes(g.n, g.nnz), dev)
     B.e2eg_sampler_prepare(g.n, g.nnz, g.row_ptr, g.col_idx, p, table, None, ws, None, _stream())
     return table
 
