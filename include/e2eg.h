@@ -101,6 +101,17 @@ int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
                        const int32_t* d_col_idx, int32_t* d_deg, float* d_dinv_sqrt,
                        void* d_sched, size_t sched_bytes, void* ws, size_t ws_bytes, void* stream);
 
+/* e2eg_sched_check_symmetric: may the transposed entry points (e2eg_propagate_bwd,
+ * e2eg_propagate_weighted_bwd, e2eg_aggregate with E2EG_AGG_MEAN_T) run on this schedule?  They
+ * apply the stored operator itself, which equals its transpose (Appendix A: the backward pass
+ * multiplies by A^T) only when every stored entry (i, j) has its mirror (j, i) - and, on a weighted
+ * graph, the same value there.  e2eg_normalize / e2eg_normalize_weighted test this while they build
+ * the schedule and keep the answer in it; this call copies it to the host.  Waits for the stream
+ * once.  Returns E2EG_OK if symmetric, E2EG_ERR_INVALID_ARG (with a message) if not.  Everything
+ * e2eg_build_csr and e2eg_edge_weights produce is symmetric, so callers on that path need not ask.
+ */
+int32_t e2eg_sched_check_symmetric(const void* d_sched, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * e2eg_propagate_fwd: H(l+1) = A^ H(l), l = 0..K-1, H(0) = X0 (Section 3.1, matrix form).
  *
@@ -129,7 +140,10 @@ int32_t e2eg_propagate_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
  * l = 0 .. K-1, layer 0 included: the backward of a loss that reads all layers with equal weight
  * (the mean readout of e2eg_readout_mean, with d_gXK holding the same array for layer K).
  * The CSR must be structurally symmetric (everything e2eg_build_csr produces is), so that
- * A^T = A^ and the same row schedule serves; this is not checked.
+ * A^T = A^ and the same row schedule serves.  e2eg_normalize finds out on the device and records it
+ * in the schedule: on a schedule whose structure is not symmetric this call still returns E2EG_OK
+ * (it reads nothing back) but every element of d_gX0 comes out NaN.  e2eg_sched_check_symmetric
+ * gives the same verdict to the host as a status code.
  */
 int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
                            const int32_t* d_col_idx, const float* d_dinv_sqrt,
@@ -145,7 +159,8 @@ int32_t e2eg_propagate_bwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
  *   E2EG_AGG_MEAN   the mean aggregator of the GraphSAGE layer (Section 3.1),
  *                   hbar_u = 1/|S(u)| sum_{v in S(u)} h_v, with S(u) = row u of a structure built
  *                   WITHOUT self-loops (the sampled neighbours); an empty row gives 0;
- *   E2EG_AGG_MEAN_T its transpose, for the backward (the structure must be symmetric);
+ *   E2EG_AGG_MEAN_T its transpose, for the backward (the structure must be symmetric: on a schedule
+ *                   that e2eg_normalize found not to be, the result is all NaN);
  *   E2EG_AGG_SYM    d_i^-1/2 d_j^-1/2 weights: one layer of e2eg_propagate_fwd;
  *   E2EG_AGG_SUM    no scaling.
  * d_X [n][F] (ldx) in, d_Y [n][F] (ldy) out, must not overlap; d_addend (may be NULL) [n][F]
@@ -245,9 +260,9 @@ int32_t e2eg_gradnorm_step(int32_t T, const double* h_loss, const double* h_loss
  * ids are out of range or that the CSR does not hold; an entry that no pair reaches stays 0.
  * Integer atomics only: the result does not depend on the order of the pairs.  Does not wait.
  *
- * e2eg_normalize_weighted: e2eg_normalize for such a graph.  d_deg_w[i] (may be NULL) = d~_i =
- * the sum of row i of d_val, added in double in a fixed order; d_dinv_sqrt[i] = (float)(1 /
- * sqrt(d~_i)), 0 where the sum is not positive.  d_sched needs e2eg_sched_weighted_bytes(n, nnz)
+ * e2eg_normalize_weighted: e2eg_normalize for such a graph.  d_deg[i] (may be NULL) = the number of
+ * stored entries of row i; d_deg_w[i] (may be NULL) = d~_i = the sum of row i of d_val, added in
+ * double in a fixed order; d_dinv_sqrt[i] = (float)(1 / sqrt(d~_i)), 0 where the sum is not positive.  d_sched needs e2eg_sched_weighted_bytes(n, nnz)
  * bytes: the unweighted schedule followed by the values in the library's own entry order.  Each
  * row must hold a column at most once (a repeat leaves one of the values out).  The workspace is
  * that of e2eg_normalize.
@@ -255,7 +270,9 @@ int32_t e2eg_gradnorm_step(int32_t T, const double* h_loss, const double* h_loss
  * e2eg_propagate_weighted_fwd / _bwd: e2eg_propagate_fwd / _bwd, argument for argument, on a
  * schedule made by e2eg_normalize_weighted; each gathered row is multiplied by its entry's value
  * (fp32 fused multiply-add).  The backward pass applies the same operator, so the values must
- * be symmetric, val(i,j) = val(j,i), which e2eg_edge_weights guarantees; this is not checked.
+ * be symmetric, val(i,j) = val(j,i), which e2eg_edge_weights guarantees; e2eg_normalize_weighted
+ * records whether they are, and the backward pass on a schedule where they are not returns all NaN
+ * (see e2eg_propagate_bwd and e2eg_sched_check_symmetric).
  * Passing a schedule of the other kind to either family is an error the library cannot detect.
  */
 int32_t e2eg_edge_weights(int32_t n_users, int32_t n_items, int64_t n_edges, const int32_t* d_user_ids,
@@ -263,8 +280,8 @@ int32_t e2eg_edge_weights(int32_t n_users, int32_t n_items, int64_t n_edges, con
                           const int32_t* d_row_ptr, const int32_t* d_col_idx, float* d_val, void* stream);
 size_t e2eg_sched_weighted_bytes(int32_t n, int64_t nnz);
 int32_t e2eg_normalize_weighted(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
-                                const float* d_val, float* d_deg_w, float* d_dinv_sqrt, void* d_sched,
-                                size_t sched_bytes, void* ws, size_t ws_bytes, void* stream);
+                                const float* d_val, int32_t* d_deg, float* d_deg_w, float* d_dinv_sqrt,
+                                void* d_sched, size_t sched_bytes, void* ws, size_t ws_bytes, void* stream);
 int32_t e2eg_propagate_weighted_fwd(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
                                     const int32_t* d_col_idx, const float* d_dinv_sqrt,
                                     const void* d_sched, int32_t dtype, int32_t F, int32_t K,
@@ -296,8 +313,8 @@ int32_t e2eg_propagate_weighted_bwd(int32_t n, int64_t nnz, const int32_t* d_row
  *
  * e2eg_sample_subgraph: hop h = 0..L-1 expands its frontier (hop 0: the distinct seeds; hop h+1:
  * the nodes first reached at hop h), each frontier node u with fan-out k = h_fanout[h] (HOST array):
- * a row of at most k stored entries keeps every entry that can be drawn; otherwise k independent
- * draws are made, draw t taking r = floor(bits * total / 2^64) with bits = words 0 (low) and 1 (high)
+ * a node with at most k neighbours (stored entries other than its own diagonal one) keeps every one
+ * that can be drawn; otherwise k independent draws are made, draw t taking r = floor(bits * total / 2^64) with bits = words 0 (low) and 1 (high)
  * of Philox4x32-10 at counter (t, u, h, 0) under key (seed low half, seed high half), and picking the
  * first entry whose running sum within the row exceeds r.  Equal draws are kept as equal pairs
  * (e2eg_build_csr counts a repeated pair once).

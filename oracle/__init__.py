@@ -21,6 +21,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "e2eg_oracle.c")
 _LIB = os.path.join(_HERE, "libe2eg_oracle.so")
+_LIB_SAN = os.path.join(_HERE, "libe2eg_oracle_san.so")
 _lib = None
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -31,20 +32,27 @@ _u32p = ctypes.POINTER(ctypes.c_uint32)
 _u64p = ctypes.POINTER(ctypes.c_uint64)
 
 
-def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (-O2, OpenMP).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP).  Returns the library path.
+
+    sanitize=True builds a second library, instrumented with AddressSanitizer and
+    UndefinedBehaviorSanitizer (any report aborts the process); a process that loads it must have
+    been started with gcc's libasan.so first in LD_PRELOAD.  The environment variable
+    E2EG_ORACLE_SANITIZE=1 makes this module load that library instead of the plain one."""
+    lib = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=all"] if sanitize else ["-O2"]
+        cmd = ["gcc"] + opt + ["-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", lib, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        sanitize = os.environ.get("E2EG_ORACLE_SANITIZE", "") == "1"
+        lib = ctypes.CDLL(build(sanitize=sanitize))
         lib.e2eg_oracle_max_threads.restype = ctypes.c_int32
         lib.e2eg_oracle_set_threads.argtypes = [ctypes.c_int32]
         lib.e2eg_oracle_build_csr.restype = ctypes.c_int64
@@ -389,6 +397,8 @@ def sampling_table(row_ptr, col_idx, p):
     """Integer weights q (uint64 [nnz]) of every row's sampling distribution; `p` is taken in float32,
     the precision in which the scaling to integers is decided."""
     row_ptr, col_idx, p = _c(row_ptr, np.int64), _c(col_idx, np.int32), _c(p, np.float32)
+    if p.size != col_idx.size or row_ptr[-1] != col_idx.size:
+        raise ValueError("one weight per stored entry is needed")
     q = np.empty(col_idx.size, dtype=np.uint64)
     _load().e2eg_oracle_sampling_table(row_ptr.size - 1, _p(row_ptr, _i64p), _p(col_idx, _i32p), _p(p, _f32p),
                                        _p(q, _u64p))

@@ -37,8 +37,8 @@
  *     gradient step on the weights and renormalisation to sum_i w_i = T.
  *   - Importance sampling of a multi-hop subgraph (Section 4.1, the sampling probability
  *     p(u->v) = w_uv^beta / sum_k w_uk^beta, at most k neighbours per node, depth L; Section 5,
- *     "Subgraph Sampling": fan-outs per hop).  A node with at most k stored neighbours keeps all that
- *     have positive weight; otherwise k independent draws are made from the distribution and equal
+ *     "Subgraph Sampling": fan-outs per hop).  A node with at most k neighbours (the diagonal entry of
+ *     its row is not one) keeps all that have positive weight; otherwise k independent draws are made from the distribution and equal
  *     draws are one neighbour.  The distribution is held in integers (weights scaled to 2^24 at the
  *     row maximum) and the random numbers come from the counter-based generator Philox4x32-10
  *     (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC 2011), so that
@@ -476,21 +476,24 @@ int64_t e2eg_oracle_sample_subgraph(int64_t n, const int64_t* row_ptr, const int
         for (int64_t u = 0; u < n; ++u) {
             if (hop_of[u] != h + 1) continue;
             const int64_t beg = row_ptr[u], end = row_ptr[u + 1];
-            for (int64_t t = 0; t < k; ++t) {
+            int64_t neighbours = 0;             /* stored entries other than the node itself */
+            for (int64_t x = beg; x < end; ++x) neighbours += col_idx[x] != u;
+            uint64_t total = 0;
+            for (int64_t x = beg; x < end; ++x) total += q[x];
+            /* at most k neighbours: every one that can be drawn at all, in stored order;
+             * more: k independent draws, draw t from the random bits of (seed, hop, node, t) */
+            const int64_t tries = neighbours <= k ? end - beg : k;
+            for (int64_t t = 0; t < tries; ++t) {
                 int64_t e = -1;
-                if (end - beg <= k) {           /* few neighbours: all that can be drawn at all */
-                    if (t < end - beg && q[beg + t] > 0) e = beg + t;
-                } else {
-                    uint64_t total = 0;
-                    for (int64_t x = beg; x < end; ++x) total += q[x];
-                    if (total > 0) {
-                        /* r uniform on [0, total): the high half of the 128-bit product bits * total */
-                        uint64_t r = (uint64_t)(((unsigned __int128)draw_bits(seed, (uint32_t)h, (uint32_t)u, (uint32_t)t) * total) >> 64);
-                        uint64_t acc = 0;
-                        for (int64_t x = beg; x < end; ++x) {
-                            acc += q[x];
-                            if (acc > r) { e = x; break; }
-                        }
+                if (neighbours <= k) {
+                    if (q[beg + t] > 0) e = beg + t;
+                } else if (total > 0) {
+                    /* r uniform on [0, total): the high half of the 128-bit product bits * total */
+                    uint64_t r = (uint64_t)(((unsigned __int128)draw_bits(seed, (uint32_t)h, (uint32_t)u, (uint32_t)t) * total) >> 64);
+                    uint64_t acc = 0;
+                    for (int64_t x = beg; x < end; ++x) {
+                        acc += q[x];
+                        if (acc > r) { e = x; break; }
                     }
                 }
                 if (e < 0) continue;

@@ -54,7 +54,8 @@ SIGNATURES = {
     "e2eg_gradnorm_step": (_i32, [_i32, _vp, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp]),
     "e2eg_edge_weights": (_i32, [_i32, _i32, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp]),
     "e2eg_sched_weighted_bytes": (_sz, [_i32, _i64]),
-    "e2eg_normalize_weighted": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_normalize_weighted": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _sz, _vp]),
+    "e2eg_sched_check_symmetric": (_i32, [_vp, _vp]),
     "e2eg_propagate_weighted_fwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _sz, _vp]),
     "e2eg_propagate_weighted_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_sampling_weights": (_i32, [_i64, _vp, ctypes.c_float, _vp, _vp]),
@@ -187,10 +188,15 @@ def e2eg_sched_weighted_bytes(n, nnz) -> int:
     return int(load_library().e2eg_sched_weighted_bytes(n, nnz))
 
 
-def e2eg_normalize_weighted(n, nnz, d_row_ptr, d_col_idx, d_val, d_deg_w, d_dinv_sqrt, d_sched, sched_bytes, ws,
-                            ws_bytes=None, stream=0):
+def e2eg_sched_check_symmetric(d_sched, stream=0):
+    """Raises E2egError (INVALID_ARG) if the schedule's structure or values are not symmetric."""
+    _check(load_library().e2eg_sched_check_symmetric(_ptr(d_sched), stream or None))
+
+
+def e2eg_normalize_weighted(n, nnz, d_row_ptr, d_col_idx, d_val, d_deg, d_deg_w, d_dinv_sqrt, d_sched, sched_bytes,
+                            ws, ws_bytes=None, stream=0):
     _check(load_library().e2eg_normalize_weighted(n, nnz, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_val),
-                                                  _ptr(d_deg_w), _ptr(d_dinv_sqrt), _ptr(d_sched),
+                                                  _ptr(d_deg), _ptr(d_deg_w), _ptr(d_dinv_sqrt), _ptr(d_sched),
                                                   _nbytes(d_sched) if sched_bytes is None else sched_bytes,
                                                   _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
                                                   stream or None))

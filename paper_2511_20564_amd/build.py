@@ -39,19 +39,6 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
-def build_measure_gather(verbose: bool = True) -> str:
-    """Builds the stand-alone gather-throughput measurement program (not needed by the library)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(HERE, "measure_gather")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", out, os.path.join(CSRC, "measure_gather.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return out
-
-
 if __name__ == "__main__":
     build()
-    build_measure_gather()
     sys.exit(0)

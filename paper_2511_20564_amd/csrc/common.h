@@ -124,11 +124,17 @@ struct SchedHeader {
     int32_t n_multi;   // rows cut into several segments
     int32_t n;
     int32_t nnz;
-    int32_t pad[2];
+    int32_t flags;     // kSchedNotSymmetric | kSchedValuesNotSymmetric, found while the schedule was built
+    int32_t pad;
     int32_t xcd_first[kXcds + 1];  // the slotted segments dealt out by equal entry counts: XCD x
                                    // owns segs[xcd_first[x] .. xcd_first[x + 1])
     int32_t pad2[7];
 };
+
+// header.flags: the stored structure holds an entry (i, j) without (j, i); the values of a weighted
+// graph differ between (i, j) and (j, i).  Either makes the transposed entry points refuse the schedule.
+constexpr int32_t kSchedNotSymmetric = 1;
+constexpr int32_t kSchedValuesNotSymmetric = 2;
 
 struct SchedView {
     SchedHeader* header;

@@ -42,12 +42,14 @@ __global__ void row_stats(const int32_t* __restrict__ row_ptr, int64_t n, int32_
 }
 
 // Sorted (degree, node) keys -> is the node one of the kTopNodes most popular, and its rank.
+// Also clears the flag that unpack_columns raises for a structure that is not symmetric.
 __global__ void mark_top(const uint64_t* __restrict__ sorted, int64_t n, int32_t* __restrict__ rank_of,
-                         int32_t* __restrict__ not_top) {
+                         int32_t* __restrict__ not_top, int32_t* __restrict__ asym) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > n) return;
     if (p == n) {
         not_top[p] = 0;
+        *asym = 0;
         return;
     }
     const int32_t i = (int32_t)(uint32_t)sorted[p];
@@ -143,7 +145,7 @@ struct RowScans {          // exclusive scans over internal rows, n + 1 entries 
 
 // Header and the list of rows that leave partial sums.  pair_off = exclusive scan of pair_nseg.
 __global__ void emit_rows(RowScans sc, const int32_t* __restrict__ pair_off, int32_t wide_rows, int32_t nwin,
-                          int32_t wide_min, int64_t n, int64_t nnz, SchedView s) {
+                          int32_t wide_min, int64_t n, int64_t nnz, const int32_t* __restrict__ asym, SchedView s) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > n) return;
     const int32_t n_slot_plain = sc.slot_off[n];
@@ -156,7 +158,8 @@ __global__ void emit_rows(RowScans sc, const int32_t* __restrict__ pair_off, int
         h.n_multi = sc.multi_off[n];
         h.n = (int32_t)n;
         h.nnz = (int32_t)nnz;
-        h.pad[0] = h.pad[1] = 0;
+        h.flags = *asym ? kSchedNotSymmetric : 0;
+        h.pad = 0;
         for (int x = 0; x <= kXcds; ++x) h.xcd_first[x] = h.n_slot;  // lowered by deal_segments
         for (int x = 0; x < 7; ++x) h.pad2[x] = 0;
         *s.header = h;
@@ -235,29 +238,30 @@ __global__ void fill_keys(uint64_t* __restrict__ keys, int64_t count) {
 // entries count kLengthCutCost / 4 times in the deal; such segments have the lowest first columns
 // and would otherwise make the first XCD's stretch the slowest.)
 __global__ void place_segments(const uint64_t* __restrict__ keys, const Segment* __restrict__ seg_tmp,
-                               SchedView s, int32_t wide_rows, int32_t wide_min, int32_t* __restrict__ seg_len) {
+                               SchedView s, int32_t wide_rows, int32_t wide_min, uint64_t* __restrict__ seg_len) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > s.max_seg) return;
-    int32_t len = 0;
+    uint64_t len = 0;
     if (p < s.header->n_seg) {
         const Segment g = seg_tmp[(uint32_t)keys[p]];
         s.segs[p] = g;
         if (p < s.header->n_slot) {
             const bool wide = g.row < wide_rows && s.zrow_ptr[g.row + 1] - s.zrow_ptr[g.row] >= wide_min;
-            len = wide ? g.end - g.beg : (g.end - g.beg) * kLengthCutCost / 4;
+            len = wide ? (uint64_t)(g.end - g.beg) : (uint64_t)(g.end - g.beg) * kLengthCutCost / 4;
         }
     }
     seg_len[p] = len;
 }
 
-// len_off = exclusive scan of seg_len (max_seg + 1 entries; the last is the total).  XCD x gets
-// the slotted segments whose running entry count starts in [x, x+1) eighths of the total.
-__global__ void deal_segments(const int32_t* __restrict__ len_off, SchedView s) {
+// len_off = exclusive scan of seg_len (max_seg + 1 entries; the last is the total; 64-bit, since
+// the weighted counts of a graph near the int32 limit of nnz pass 2^31).  XCD x gets the slotted
+// segments whose running entry count starts in [x, x+1) eighths of the total.
+__global__ void deal_segments(const uint64_t* __restrict__ len_off, SchedView s) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int32_t n_slot = s.header->n_slot;
     if (p >= n_slot) return;
-    const int64_t total = len_off[s.max_seg];
-    const int64_t here = len_off[p], prev = p > 0 ? len_off[p - 1] : -1;
+    const int64_t total = (int64_t)len_off[s.max_seg];
+    const int64_t here = (int64_t)len_off[p], prev = p > 0 ? (int64_t)len_off[p - 1] : -1;
     for (int x = 0; x < kXcds; ++x) {
         const int64_t mark = total * x / kXcds;   // first segment whose start count is >= mark
         if (here >= mark && prev < mark) s.header->xcd_first[x] = (int32_t)p;
@@ -299,10 +303,27 @@ __global__ __launch_bounds__(kThreads) void entry_keys(const int32_t* __restrict
     keys[e] = ((uint64_t)(uint32_t)zpos[row] << bits) | (uint32_t)zpos[col_idx[e]];
 }
 
+// Sorted (row, column) keys -> the column array.  The same pass looks for the mirror image of every
+// entry (the key (column, row), by binary search in that row's stretch of the sorted keys): the
+// transposed entry points run on this schedule only if the structure is symmetric.
 __global__ void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, int bits,
-                               int32_t* __restrict__ zcol) {
+                               const int32_t* __restrict__ zrow_ptr, int32_t* __restrict__ zcol,
+                               int32_t* __restrict__ asym) {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < nnz) zcol[e] = (int32_t)(keys[e] & ((1ull << bits) - 1));
+    if (e >= nnz) return;
+    const uint64_t key = keys[e];
+    const uint32_t c = (uint32_t)(key & ((1ull << bits) - 1));
+    const uint32_t r = (uint32_t)(key >> bits);
+    zcol[e] = (int32_t)c;
+    if (r == c) return;
+    const uint64_t mirror = ((uint64_t)c << bits) | r;
+    int32_t lo = zrow_ptr[c], hi = zrow_ptr[c + 1];   // first position with key >= mirror
+    const int32_t end = hi;
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid] < mirror) lo = mid + 1; else hi = mid;
+    }
+    if (lo >= end || keys[lo] != mirror) atomicOr(asym, 1);
 }
 
 // Weighted graphs.  d~_i = sum of the stored values of row i (the diagonal entry carries the 1 of
@@ -349,6 +370,18 @@ __global__ __launch_bounds__(kThreads) void place_values(const int32_t* __restri
         if (s.zcol[mid] < c) a = mid + 1; else b = mid;
     }
     if (a < s.zrow_ptr[p + 1] && s.zcol[a] == c) s.zval[a] = val[e];
+    // the mirror entry (j, i) of the caller's CSR must carry the same value (bit for bit), or the
+    // transposed entry points would apply another operator than the transpose
+    const int32_t j = col_idx[e];
+    if (j == (int32_t)lo) return;
+    int32_t ma = row_ptr[j], mb = row_ptr[j + 1];   // first position in row j with column >= i
+    const int32_t mend = mb;
+    while (ma < mb) {
+        const int32_t mid = ma + ((mb - ma) >> 1);
+        if (col_idx[mid] < (int32_t)lo) ma = mid + 1; else mb = mid;
+    }
+    if (ma >= mend || col_idx[ma] != (int32_t)lo || __float_as_uint(val[ma]) != __float_as_uint(val[e]))
+        atomicOr(&s.header->flags, kSchedValuesNotSymmetric);
 }
 
 __global__ void zero_values(float* __restrict__ v, int64_t count) {
@@ -368,7 +401,8 @@ struct NormWs {
     int32_t* is_multi;
     int32_t* bounds;     // [wide rows][windows + 1]
     int32_t* pair_nseg;  // [wide rows * windows + 1]
-    int32_t* seg_len;    // [max_seg + 1]
+    uint64_t* seg_len;   // [max_seg + 1]
+    int32_t* asym;       // [1] raised when the structure is not symmetric
     Segment* seg_tmp;
     void* scan_ws;
     void* sort_ws;
@@ -392,7 +426,8 @@ NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     w.is_multi = c.take<int32_t>(n + 1);
     w.bounds = c.take<int32_t>(sched_max_wide_rows(n) * (sched_windows(n) + 1) + 1);
     w.pair_nseg = c.take<int32_t>(sched_max_pairs(n) + 1);
-    w.seg_len = c.take<int32_t>(max_seg + 1);
+    w.seg_len = c.take<uint64_t>(max_seg + 1);
+    w.asym = c.take<int32_t>(1);
     w.seg_tmp = c.take<Segment>(max_seg);
     w.scan_ws = c.take<char>(5 * scan_workspace_bytes(m));   // the five row scans share one set of launches
     w.sort_ws = c.take<char>(radix_sort_workspace_bytes(m));
@@ -424,7 +459,7 @@ extern "C" size_t e2eg_normalize_workspace_bytes(int32_t n, int64_t nnz) {
 
 namespace {
 // d_val == nullptr: the unweighted call.  Otherwise d~ and d~^-1/2 come from the values (d_deg_w may
-// be null), d_deg is not written, and the schedule also receives the values in internal order.
+// be null), d_deg receives the row lengths, and the schedule also receives the values in internal order.
 int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                        const float* d_val, int32_t* d_deg, float* d_deg_w, float* d_dinv_sqrt, void* d_sched,
                        size_t sched_bytes, void* ws, size_t ws_bytes, void* stream_) {
@@ -456,7 +491,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         int32_t st = radix_sort_u64(&src, &dst, n, 32, bits_for((int64_t)n + 1), w.sort_ws, stream);
         if (st != E2EG_OK) return st;
     }
-    mark_top<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(src, n, w.rank_of, w.not_top);
+    mark_top<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(src, n, w.rank_of, w.not_top, w.asym);
     E2EG_LAUNCH_CHECK("mark_top");
     E2EG_HIP_TRY(exclusive_scan_i32(w.not_top, w.not_top, (int64_t)n + 1, nullptr, w.scan_ws, stream));
     src = w.keys_a;
@@ -489,7 +524,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         E2EG_LAUNCH_CHECK("entry_keys");
         int32_t st = radix_sort_u64(&src, &dst, nnz, 0, 2 * bits, w.sort_ws, stream);
         if (st != E2EG_OK) return st;
-        unpack_columns<<<grid_for(nnz), blk, 0, stream>>>(src, nnz, bits, view.zcol);
+        unpack_columns<<<grid_for(nnz), blk, 0, stream>>>(src, nnz, bits, view.zrow_ptr, view.zcol, w.asym);
         E2EG_LAUNCH_CHECK("unpack_columns");
     }
 
@@ -504,7 +539,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         E2EG_LAUNCH_CHECK("wide_counts");
         E2EG_HIP_TRY(exclusive_scan_i32(w.pair_nseg, w.pair_nseg, pairs + 1, nullptr, w.scan_ws, stream));
     }
-    emit_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(sc, w.pair_nseg, wide_rows, nwin, wide_min, n, nnz, view);
+    emit_rows<<<grid_for((int64_t)n + 1), blk, 0, stream>>>(sc, w.pair_nseg, wide_rows, nwin, wide_min, n, nnz, w.asym, view);
     E2EG_LAUNCH_CHECK("emit_rows");
     if (nnz > kShortMax) {  // otherwise no row can be long
         src = w.keys_a;
@@ -523,7 +558,7 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
         if (st != E2EG_OK) return st;
         place_segments<<<grid_for(view.max_seg + 1), blk, 0, stream>>>(src, w.seg_tmp, view, wide_rows, wide_min, w.seg_len);
         E2EG_LAUNCH_CHECK("place_segments");
-        E2EG_HIP_TRY(exclusive_scan_i32(w.seg_len, w.seg_len, view.max_seg + 1, nullptr, w.scan_ws, stream));
+        E2EG_HIP_TRY(exclusive_scan_u64(w.seg_len, w.seg_len, view.max_seg + 1, nullptr, w.scan_ws, stream));
         deal_segments<<<grid_for(view.max_slot + 1), blk, 0, stream>>>(w.seg_len, view);
         E2EG_LAUNCH_CHECK("deal_segments");
     }
@@ -554,11 +589,26 @@ extern "C" int32_t e2eg_normalize(int32_t n, int64_t nnz, const int32_t* d_row_p
 }
 
 extern "C" int32_t e2eg_normalize_weighted(int32_t n, int64_t nnz, const int32_t* d_row_ptr,
-                                           const int32_t* d_col_idx, const float* d_val, float* d_deg_w,
-                                           float* d_dinv_sqrt, void* d_sched, size_t sched_bytes, void* ws,
-                                           size_t ws_bytes, void* stream) {
+                                           const int32_t* d_col_idx, const float* d_val, int32_t* d_deg,
+                                           float* d_deg_w, float* d_dinv_sqrt, void* d_sched, size_t sched_bytes,
+                                           void* ws, size_t ws_bytes, void* stream) {
     if (!d_val && nnz > 0) return fail(E2EG_ERR_NULL_PTR, "normalize_weighted: d_val is null");
     static const float kOne = 1.0f;  // nnz == 0: any non-null pointer selects the weighted layout
-    return normalize_impl(n, nnz, d_row_ptr, d_col_idx, d_val ? d_val : &kOne, nullptr, d_deg_w, d_dinv_sqrt, d_sched,
+    return normalize_impl(n, nnz, d_row_ptr, d_col_idx, d_val ? d_val : &kOne, d_deg, d_deg_w, d_dinv_sqrt, d_sched,
                           sched_bytes, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_sched_check_symmetric(const void* d_sched, void* stream_) {
+    if (!d_sched) return fail(E2EG_ERR_NULL_PTR, "sched_check_symmetric: d_sched is null");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    SchedHeader h;   // the schedule starts with its header
+    E2EG_HIP_TRY(hipMemcpyAsync(&h, d_sched, sizeof(h), hipMemcpyDeviceToHost, stream));
+    E2EG_HIP_TRY(hipStreamSynchronize(stream));
+    if (h.flags & kSchedNotSymmetric)
+        return fail(E2EG_ERR_INVALID_ARG, "sched_check_symmetric: the structure holds an entry (i, j) without (j, i); "
+                                          "the transposed entry points cannot run on it");
+    if (h.flags & kSchedValuesNotSymmetric)
+        return fail(E2EG_ERR_INVALID_ARG, "sched_check_symmetric: the values of (i, j) and (j, i) differ somewhere; "
+                                          "the transposed entry points cannot run on it");
+    return E2EG_OK;
 }

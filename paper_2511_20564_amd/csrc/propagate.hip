@@ -532,6 +532,11 @@ constexpr int kPrescaleRows = 4;   // rows per thread: their dependent loads (ro
 
 // Z(0) = S X(0) in internal row order: one streaming pass, 16 bytes of kPrescaleRows rows per
 // thread.  Also clears the zero rows (index n) of both Z buffers.
+// `transposed_of` is the schedule's header when the pass computes with the TRANSPOSE of the stored
+// operator (the backward entry points), else null.  Those entry points apply the stored operator
+// itself, which is its transpose only if structure and values are symmetric; a schedule that
+// e2eg_normalize found not to be is refused here, on the device, without a read-back: every row of
+// Z(0) becomes NaN, and so does the whole result.
 template <typename T>
 __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename T::elem* __restrict__ x,
                                                                    int64_t ldx,
@@ -539,7 +544,8 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
                                                                    const int32_t* __restrict__ orig,
                                                                    typename T::elem* __restrict__ z,
                                                                    typename T::elem* __restrict__ z_other,
-                                                                   int64_t n, int32_t F) {
+                                                                   int64_t n, int32_t F,
+                                                                   const SchedHeader* __restrict__ transposed_of) {
     constexpr int V = T::kVec;
     const int chunks = F / V;
     const int64_t id = (int64_t)blockIdx.x * kPrescaleThreads + threadIdx.x;
@@ -565,12 +571,17 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
             s[i] = dinv_sqrt[node[i]];
         }
     }
+    const bool refuse = transposed_of != nullptr && transposed_of->flags != 0;
 #pragma unroll
     for (int i = 0; i < kPrescaleRows; ++i) {
         const int64_t zrow = group * kPrescaleRows + i;
         if (zrow > n) continue;
 #pragma unroll
         for (int k = 0; k < V; ++k) v[i][k] *= s[i];   // the zero row: 0 * 0
+        if (refuse && zrow < n) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) v[i][k] = __builtin_nanf("");
+        }
         store_vec<T>(z + zrow * F + col, v[i]);
         if (zrow == n && z_other) store_vec<T>(z_other + zrow * F + col, v[i]);
     }
@@ -676,7 +687,7 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
                    const float* dinv, const void* sched, int32_t F, int32_t K, const void* in,
                    int64_t ld_in, typename T::elem* const* store, const int64_t* ld_store,
                    const typename T::elem* const* add, int64_t ld_add, const PropWs& w,
-                   bool weighted, hipStream_t stream) {
+                   bool weighted, bool transposed, hipStream_t stream) {
     using E = typename T::elem;
     SchedView view;
     sched_carve(const_cast<void*>(sched), n, nnz, &view, weighted);
@@ -685,7 +696,7 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     E* z_next = static_cast<E*>(w.z[1]);
     prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig, z_cur,
-                                                            z_next, n, F);
+                                                            z_next, n, F, transposed ? view.header : nullptr);
     E2EG_LAUNCH_CHECK("prescale_rows");
     for (int32_t l = 1; l <= K; ++l) {
         LayerArgs<T> a;
@@ -757,7 +768,8 @@ int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_p
     const int chunks = F / T::kVec;
     prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(x), ldx, w.scale_in, view.orig,
-                                                            static_cast<E*>(w.z), nullptr, n, F);
+                                                            static_cast<E*>(w.z), nullptr, n, F,
+                                                            mode == E2EG_AGG_MEAN_T ? view.header : nullptr);
     E2EG_LAUNCH_CHECK("prescale_rows");
     LayerArgs<T> a;
     a.dinv_sqrt = w.scale_out;
@@ -818,14 +830,14 @@ int32_t propagate_fwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t*
             store[l - 1] = layer_stride ? static_cast<float*>(d_Xout) + (int64_t)(l - 1) * layer_stride
                                         : (l == K ? static_cast<float*>(d_Xout) : nullptr);
         return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
-                               lds, nullptr, 0, w, weighted, stream);
+                               lds, nullptr, 0, w, weighted, false, stream);
     }
     uint16_t* store[kMaxLayers];
     for (int l = 1; l <= K; ++l)
         store[l - 1] = layer_stride ? static_cast<uint16_t*>(d_Xout) + (int64_t)(l - 1) * layer_stride
                                     : (l == K ? static_cast<uint16_t*>(d_Xout) : nullptr);
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_X0, ldx, store,
-                            lds, nullptr, 0, w, weighted, stream);
+                            lds, nullptr, 0, w, weighted, false, stream);
 }
 
 int32_t propagate_bwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t* d_row_ptr,
@@ -868,7 +880,7 @@ int32_t propagate_bwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t*
                                                  : nullptr;
         }
         return run_layers<F32>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
-                               lds, add, ldg, w, weighted, stream);
+                               lds, add, ldg, w, weighted, true, stream);
     }
     uint16_t* store[kMaxLayers];
     const uint16_t* add[kMaxLayers];
@@ -880,7 +892,7 @@ int32_t propagate_bwd_impl(bool weighted, int32_t n, int64_t nnz, const int32_t*
                                              : nullptr;
     }
     return run_layers<BF16>(n, nnz, d_row_ptr, d_col_idx, d_dinv_sqrt, d_sched, F, K, d_gXK, ldg, store,
-                            lds, add, ldg, w, weighted, stream);
+                            lds, add, ldg, w, weighted, true, stream);
 }
 }  // namespace
 

@@ -183,8 +183,23 @@ __global__ void draw_picks(const int32_t* __restrict__ row_ptr, const int32_t* _
     if (f < *front_count) {
         u = frontier[f];
         const int32_t beg = row_ptr[u], end = row_ptr[u + 1];
-        if (end - beg <= k) {  // few neighbours: every one that can be drawn at all
+        // A node with at most k neighbours keeps every one that can be drawn at all.  Its row may
+        // also hold the node itself (the diagonal entry, never drawn), so a row of k + 1 entries
+        // qualifies when one of them is the diagonal: slot t then takes the t-th entry beside it.
+        int32_t diag = -1;   // where the diagonal entry sits, looked for only where it decides
+        if (end - beg == k + 1) {
+            int32_t lo = beg, hi = end;   // first entry with column >= u (columns ascend)
+            while (lo < hi) {
+                const int32_t mid = lo + ((hi - lo) >> 1);
+                if (col_idx[mid] < u) lo = mid + 1; else hi = mid;
+            }
+            if (lo < end && col_idx[lo] == u) diag = lo;
+        }
+        if (end - beg <= k) {
             if (t < end - beg && cum[beg + t + 1] > cum[beg + t]) ent = beg + t;
+        } else if (diag >= 0) {
+            const int32_t e = beg + t + (beg + t >= diag ? 1 : 0);
+            if (cum[e + 1] > cum[e]) ent = e;
         } else {
             const uint64_t base = cum[beg], total = cum[end] - base;
             if (total > 0) {

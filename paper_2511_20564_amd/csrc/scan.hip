@@ -2,7 +2,7 @@
 // offsets, the row schedule) and over uint64 (cumulative sampling weights).  Large inputs take
 // three launches: per-tile sums, a one-block scan of those sums, per-tile scan plus tile offset.
 // Small graphs are bound by the number of launches, so up to 1024 tiles every workgroup adds up
-// the sums of the tiles before it by itself (two launches), and up to 16 tiles one workgroup
+// the sums of the tiles before it by itself (two launches), and up to 4 tiles one workgroup
 // scans everything (one launch).  Integer arithmetic only, so the result does not depend on
 // scheduling.
 #include "common.h"

@@ -60,6 +60,12 @@ def normalize(n: int, nnz: int, row_ptr: torch.Tensor, col_idx: torch.Tensor):
     return deg, dinv, sched
 
 
+def check_symmetric(sched: torch.Tensor) -> None:
+    """e2eg_sched_check_symmetric: raises if the transposed entry points cannot run on `sched`."""
+    _require_gpu()
+    B.e2eg_sched_check_symmetric(sched, _stream())
+
+
 def build_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Tensor,
                 add_self_loops: bool = True) -> Graph:
     """e2eg_build_csr followed by e2eg_normalize.  `users`/`items`: int32 device tensors."""
@@ -82,16 +88,17 @@ def build_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Te
 
 
 def normalize_weighted(n: int, nnz: int, row_ptr: torch.Tensor, col_idx: torch.Tensor, val: torch.Tensor):
-    """e2eg_normalize_weighted on an existing CSR with values -> (deg_w, dinv_sqrt, sched)."""
+    """e2eg_normalize_weighted on an existing CSR with values -> (deg, deg_w, dinv_sqrt, sched)."""
     _require_gpu()
     assert val.dtype == torch.float32 and val.is_contiguous() and val.numel() >= nnz
     dev = row_ptr.device
+    deg = torch.empty(n, dtype=torch.int32, device=dev)
     deg_w = torch.empty(n, dtype=torch.float32, device=dev)
     dinv = torch.empty(n, dtype=torch.float32, device=dev)
     sched = _bytes(B.e2eg_sched_weighted_bytes(n, nnz), dev)
     ws = _bytes(B.e2eg_normalize_workspace_bytes(n, nnz), dev)
-    B.e2eg_normalize_weighted(n, nnz, row_ptr, col_idx, val, deg_w, dinv, sched, None, ws, None, _stream())
-    return deg_w, dinv, sched
+    B.e2eg_normalize_weighted(n, nnz, row_ptr, col_idx, val, deg, deg_w, dinv, sched, None, ws, None, _stream())
+    return deg, deg_w, dinv, sched
 
 
 def build_weighted_graph(n_users: int, n_items: int, users: torch.Tensor, items: torch.Tensor,
@@ -115,8 +122,7 @@ def build_weighted_graph(n_users: int, n_items: int, users: torch.Tensor, items:
     col_idx = col[:nnz]
     val = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)[:nnz]
     B.e2eg_edge_weights(n_users, n_items, n_edges, users, items, weights, nnz, row_ptr, col_idx, val, _stream())
-    deg_w, dinv, sched = normalize_weighted(n, nnz, row_ptr, col_idx, val)
-    deg = (row_ptr[1:] - row_ptr[:-1]).to(torch.int32)
+    deg, deg_w, dinv, sched = normalize_weighted(n, nnz, row_ptr, col_idx, val)
     return Graph(n_users, n_items, n, nnz, row_ptr, col_idx, deg, dinv, sched, val, deg_w)
 
 

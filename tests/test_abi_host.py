@@ -227,10 +227,11 @@ def test_weighted_graph_argument_errors(B):
     assert B.e2eg_sched_weighted_bytes(-1, 0) == 0
     nw = B.e2eg_normalize_weighted
     big = 1 << 30
-    assert status_of(B, nw, 10, 30, FAKE, FAKE, None, None, FAKE, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
-    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, None, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
-    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, FAKE, FAKE, B.e2eg_sched_bytes(10, 30), FAKE, big) == B.E2EG_ERR_CAPACITY
-    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, FAKE, FAKE, big, FAKE, 16) == B.E2EG_ERR_WORKSPACE
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, None, None, None, FAKE, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, None, None, FAKE, big, FAKE, big) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, B.e2eg_sched_bytes(10, 30), FAKE, big) == B.E2EG_ERR_CAPACITY
+    assert status_of(B, nw, 10, 30, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, big, FAKE, 16) == B.E2EG_ERR_WORKSPACE
+    assert status_of(B, B.e2eg_sched_check_symmetric, None) == B.E2EG_ERR_NULL_PTR
     f = B.e2eg_propagate_weighted_fwd
     assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, FAKE, B.E2EG_F32, 6, 2, FAKE, 8, FAKE, 8, 0, FAKE, big) == B.E2EG_ERR_INVALID_ARG
     assert status_of(B, f, 10, 30, FAKE, FAKE, FAKE, None, B.E2EG_F32, 8, 2, FAKE, 8, FAKE, 8, 0, FAKE, big) == B.E2EG_ERR_NULL_PTR

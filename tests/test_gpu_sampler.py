@@ -101,6 +101,25 @@ def test_sampler_edge_cases(dev, oracle):
     assert e.value.status == dev.B.E2EG_ERR_BAD_INDEX
 
 
+def test_nodes_with_exactly_k_neighbours_keep_them_all(dev, oracle):
+    """A node that has exactly as many neighbours as the fan-out allows keeps every one (its row holds
+    one entry more: itself), on the user side (diagonal first) and the item side (diagonal last)."""
+    nu, ni, ne = 40, 30, 300
+    users, items = uniform_bipartite(nu, ni, ne, seed=8)
+    w = make_edge_weights(ne, seed=9)
+    g, row_ptr, col, val = parent(dev, oracle, nu, ni, users, items, w)
+    deg = np.diff(row_ptr) - 1
+    seeds = np.arange(nu, dtype=np.int32)
+    for fan in ([7, 10], [8, 9, 7], [6, 11]):
+        assert (deg[:nu] == fan[0]).any() and (deg[nu:] == fan[1]).any()
+        s, r = check_sample(dev, oracle, g, row_ptr, col, val, val.astype(np.float32), seeds, fan, seed=5)
+        # hop 0 expands every user: a user with exactly fan[0] items has all of them among the pairs
+        gu, gi = r["nodes"][r["users"]], r["nodes"][r["n_users"] + r["items"]]
+        for u in np.nonzero(deg[:nu] == fan[0])[0]:
+            want = col[row_ptr[u] + 1:row_ptr[u + 1]]
+            assert set(want.tolist()) <= set(gi[gu == u].tolist())
+
+
 @pytest.mark.parametrize("beta", [0.0, 1.0, 0.5, 1.7])
 def test_sampling_weights(dev, oracle, beta):
     c = make_config(1, features=False)

@@ -749,7 +749,7 @@ def test_sampling_table_is_the_distribution_in_integers(oracle):
             assert np.allclose(q[sl][ok] / q[sl][ok].sum(), pr / pr.sum(), rtol=2e-5)
     # a weight far below the row maximum keeps the smallest positive chance instead of none
     row_ptr, col, _ = one_user_graph(oracle, [1.0, 1.0])
-    q = oracle.sampling_table(row_ptr, col, np.array([0.0, 1.0, 1e-12, 1.0, 1.0], np.float32)[:col.size])
+    q = oracle.sampling_table(row_ptr, col, np.array([0.0, 1.0, 1e-12, 1.0, 1.0, 1.0, 1.0], np.float32))
     assert sorted(q[row_ptr[0]:row_ptr[1]].tolist()) == [0, 1, 1 << 24]
 
 
@@ -810,6 +810,35 @@ def test_sampler_large_beta_keeps_the_strongest_neighbour(oracle):
     assert dst.tolist() == [4, 4, 4, 4]                     # item 3 = node 4; (2.9/3)^2000 is below 2^-24
 
 
+def test_sampler_keeps_all_of_exactly_k_neighbours(oracle):
+    """Section 4.1 caps a node at k neighbours: a node that has exactly k keeps every one of them (no
+    draws with replacement, which would lose some), whichever end of the row its own diagonal entry
+    sits at; with k + 1 neighbours k draws are made."""
+    for k in (1, 3, 7):
+        w = np.linspace(0.5, 2.0, k)
+        row_ptr, col, val = one_user_graph(oracle, w)                  # user 0: diagonal first, then k items
+        q = oracle.sampling_table(row_ptr, col, val.astype(np.float32))
+        _, src, dst, _ = oracle.sample_picks(row_ptr, col, q, [0], [k], 11)
+        assert src.tolist() == [0] * k and dst.tolist() == list(range(1, k + 1))
+        # an item with exactly k users: its diagonal entry is the LAST of its row
+        u, i = np.arange(k, dtype=np.int32), np.zeros(k, np.int32)
+        rp, cl = oracle.build_csr(k, 1, u, i)
+        vv = oracle.edge_values(k, u, i, w, rp, cl)
+        qq = oracle.sampling_table(rp, cl, vv.astype(np.float32))
+        _, src, dst, _ = oracle.sample_picks(rp, cl, qq, [k], [k], 11)
+        assert src.tolist() == [k] * k and dst.tolist() == list(range(k))
+        # one more neighbour than k: k draws (with replacement, so possibly fewer distinct ones)
+        row_ptr, col, val = one_user_graph(oracle, np.linspace(0.5, 2.0, k + 1))
+        q = oracle.sampling_table(row_ptr, col, val.astype(np.float32))
+        _, src, dst, _ = oracle.sample_picks(row_ptr, col, q, [0], [k], 11)
+        assert dst.size == k and set(dst.tolist()) <= set(range(1, k + 2))
+    # a weight that cannot be drawn stays out even when every neighbour is kept
+    row_ptr, col, val = one_user_graph(oracle, [1.0, 0.0, 2.0])
+    q = oracle.sampling_table(row_ptr, col, val.astype(np.float32))
+    _, _, dst, _ = oracle.sample_picks(row_ptr, col, q, [0], [3], 11)
+    assert dst.tolist() == [1, 3]
+
+
 def test_sampler_structure(oracle):
     """Two hops on a power-law graph: what must hold for any random bits."""
     c = make_config(2, scale=0.02, features=False)
@@ -839,8 +868,8 @@ def test_sampler_structure(oracle):
         for u in frontier:
             mine = np.sort(entry[sel & (src == u)])
             usable = np.arange(row_ptr[u], row_ptr[u + 1])[q[row_ptr[u]:row_ptr[u + 1]] > 0]
-            if deg[u] <= k:
-                assert np.array_equal(mine, usable)                                    # few neighbours: all of them
+            if deg[u] - 1 <= k:                                                       # the row also holds the node itself
+                assert np.array_equal(mine, usable)                                    # at most k neighbours: all of them
             else:
                 assert mine.size == (k if usable.size else 0)                          # else exactly k draws
         reached = np.nonzero(hop_of == h + 2)[0]                                       # first reached at this hop
