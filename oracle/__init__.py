@@ -58,6 +58,12 @@ def _load():
         lib.e2eg_oracle_build_csr.restype = ctypes.c_int64
         lib.e2eg_oracle_build_csr.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _i32p, _i32p,
                                               ctypes.c_int32, _i64p, _i32p]
+        lib.e2eg_oracle_build_csr_rows.restype = ctypes.c_int64
+        lib.e2eg_oracle_build_csr_rows.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _i32p, _i32p,
+                                                   ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, _i64p, _i32p,
+                                                   ctypes.c_int64]
+        lib.e2eg_oracle_transposed_to_targets.argtypes = [ctypes.c_int64, ctypes.c_int64, _i64p, _i32p, _i64p,
+                                                          ctypes.c_int64, _f64p, ctypes.c_int64, _i64p, _f64p]
         lib.e2eg_oracle_normalize.argtypes = [ctypes.c_int64, _i64p, _i64p, _f64p]
         lib.e2eg_oracle_propagate_layer.argtypes = [ctypes.c_int64, _i64p, _i32p, ctypes.c_int64, _f64p, _f64p]
         lib.e2eg_oracle_propagate_layer_transposed.argtypes = lib.e2eg_oracle_propagate_layer.argtypes
@@ -188,6 +194,46 @@ def propagate_rows(row_ptr, col_idx, X, rows):
     _load().e2eg_oracle_propagate_rows(rows.size, _p(rows, _i64p), _p(row_ptr, _i64p), _p(col_idx, _i32p),
                                        F, _p(X, _f64p), _p(Y, _f64p))
     return Y
+
+
+def build_csr_rows(n_users, n_items, users, items, row_lo, row_hi, add_self_loops=True):
+    """Rows row_lo <= r < row_hi of the canonical CSR of A~ -> (row_ptr_local int64 starting at 0,
+    col_idx int32), built from the pair list alone."""
+    users = _c(users, np.int32)
+    items = _c(items, np.int32)
+    if users.shape != items.shape or users.ndim != 1:
+        raise ValueError("users/items must be 1-D arrays of equal length")
+    rows = int(row_hi) - int(row_lo)
+    if rows < 0:
+        raise ValueError("empty or reversed row range")
+    row_ptr = np.zeros(rows + 1, dtype=np.int64)
+    col = np.empty(0, dtype=np.int32)
+    for _ in range(2):          # first call sizes the column array, second fills it
+        nnz = _load().e2eg_oracle_build_csr_rows(n_users, n_items, users.size, _p(users, _i32p), _p(items, _i32p),
+                                                 1 if add_self_loops else 0, int(row_lo), int(row_hi),
+                                                 _p(row_ptr, _i64p), _p(col, _i32p), col.size)
+        if nnz < 0:
+            raise ValueError("bad row range, user or item id out of range, or out of memory")
+        if nnz <= col.size:
+            break
+        col = np.empty(nnz, dtype=np.int32)
+    return row_ptr, col[:nnz]
+
+
+def transposed_to_targets(row_lo, row_ptr_local, col_idx_local, deg, Gnext, targets, out):
+    """out += contributions of the source rows [row_lo, row_lo + rows) to (A^T Gnext)[targets];
+    `targets` ascending node ids, `deg` = d~ of every node, `out` float64 [len(targets), F]."""
+    row_ptr_local, col_idx_local = _c(row_ptr_local, np.int64), _c(col_idx_local, np.int32)
+    deg, targets = _c(deg, np.int64), _c(targets, np.int64)
+    if Gnext.dtype != np.float64 or not Gnext.flags.c_contiguous or out.dtype != np.float64 or not out.flags.c_contiguous:
+        raise ValueError("Gnext and out must be C-contiguous float64 arrays")
+    if targets.size > 1 and (np.diff(targets) <= 0).any():
+        raise ValueError("targets must be strictly ascending")
+    F = Gnext.shape[1]
+    assert out.shape == (targets.size, F) and row_ptr_local[-1] == col_idx_local.size
+    _load().e2eg_oracle_transposed_to_targets(int(row_lo), row_ptr_local.size - 1, _p(row_ptr_local, _i64p),
+                                              _p(col_idx_local, _i32p), _p(deg, _i64p), F, _p(Gnext, _f64p),
+                                              targets.size, _p(targets, _i64p), _p(out, _f64p))
 
 
 def propagate_fwd(row_ptr, col_idx, X0, K):

@@ -116,6 +116,50 @@ int64_t e2eg_oracle_build_csr(int32_t n_users, int32_t n_items, int64_t n_edges,
     return nnz;
 }
 
+/*
+ * The same structure for the rows row_lo <= r < row_hi only (for graphs whose full entry list is
+ * better not sorted in one piece): list every (row, col) entry whose row is in the range, sort,
+ * drop repeats.  row_ptr_local has row_hi - row_lo + 1 entries and starts at 0; col_idx has room
+ * for `cap` entries.  Returns the number of entries of the range (even when it exceeds cap, in
+ * which case nothing is written beyond cap and the caller asks again), or -1 on an
+ * out-of-range id / allocation failure.
+ */
+int64_t e2eg_oracle_build_csr_rows(int32_t n_users, int32_t n_items, int64_t n_edges, const int32_t* users,
+                                   const int32_t* items, int32_t add_self_loops, int64_t row_lo, int64_t row_hi,
+                                   int64_t* row_ptr_local, int32_t* col_idx, int64_t cap) {
+    int64_t n = (int64_t)n_users + n_items;
+    if (row_lo < 0 || row_hi > n || row_lo > row_hi) return -1;
+    int64_t listed = 0;
+    for (int64_t e = 0; e < n_edges; ++e) {
+        int64_t u = users[e], i = items[e];
+        if (u < 0 || u >= n_users || i < 0 || i >= n_items) return -1;
+        listed += (u >= row_lo && u < row_hi) + (n_users + i >= row_lo && n_users + i < row_hi);
+    }
+    if (add_self_loops) listed += row_hi - row_lo;
+    uint64_t* key = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(listed > 0 ? listed : 1));
+    if (!key) return -1;
+    int64_t m = 0;
+    for (int64_t e = 0; e < n_edges; ++e) {
+        uint64_t a = (uint64_t)users[e], b = (uint64_t)n_users + (uint64_t)items[e];
+        if ((int64_t)a >= row_lo && (int64_t)a < row_hi) key[m++] = (a << 32) | b;   /* A[u][nu+i] */
+        if ((int64_t)b >= row_lo && (int64_t)b < row_hi) key[m++] = (b << 32) | a;   /* A[nu+i][u] */
+    }
+    if (add_self_loops)
+        for (int64_t v = row_lo; v < row_hi; ++v) key[m++] = ((uint64_t)v << 32) | (uint64_t)v;  /* + I */
+    qsort(key, (size_t)m, sizeof(uint64_t), cmp_u64);
+    int64_t nnz = 0;
+    for (int64_t r = 0; r <= row_hi - row_lo; ++r) row_ptr_local[r] = 0;
+    for (int64_t k = 0; k < m; ++k) {
+        if (k > 0 && key[k] == key[k - 1]) continue;   /* repeated pair: one edge */
+        if (nnz < cap) col_idx[nnz] = (int32_t)(key[k] & 0xffffffffu);
+        ++nnz;
+        row_ptr_local[(int64_t)(key[k] >> 32) - row_lo + 1] += 1;
+    }
+    for (int64_t r = 0; r < row_hi - row_lo; ++r) row_ptr_local[r + 1] += row_ptr_local[r];
+    free(key);
+    return nnz;
+}
+
 /* d~_i = sum_j A~_ij = number of stored entries in row i;  s_i = d~_i^-1/2 (0 for an
  * empty row, which can only occur without self-loops). */
 void e2eg_oracle_normalize(int64_t n, const int64_t* row_ptr, int64_t* deg, double* dinv_sqrt) {
@@ -161,6 +205,35 @@ void e2eg_oracle_propagate_rows(int64_t n_rows, const int64_t* rows, const int64
             double a = a_hat(row_ptr, i, j);
             const double* x = X + j * F;
             for (int64_t f = 0; f < F; ++f) y[f] += a * x[f];
+        }
+    }
+}
+
+/*
+ * The backward's scatter (G_j += A^_ij Gnext_i for every stored (i, j): Appendix A, the "GNN backprop"
+ * factor) restricted to chosen target nodes j and to the source rows row_lo <= i < row_lo + n_rows,
+ * whose entries are given as a local CSR (row_ptr_local starting at 0).  deg[v] = d~_v for every node.
+ * targets are ascending node ids; out[t] (n_targets x F) is ADDED to, so that calls over consecutive
+ * row ranges build up (A^T Gnext)[targets].  No symmetry is assumed: an entry (i, j) feeds node j only.
+ */
+void e2eg_oracle_transposed_to_targets(int64_t row_lo, int64_t n_rows, const int64_t* row_ptr_local,
+                                       const int32_t* col_idx_local, const int64_t* deg, int64_t F,
+                                       const double* Gnext, int64_t n_targets, const int64_t* targets,
+                                       double* out) {
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int64_t i = row_lo + r;
+        const double* g = Gnext + i * F;
+        for (int64_t p = row_ptr_local[r]; p < row_ptr_local[r + 1]; ++p) {
+            const int64_t j = col_idx_local[p];
+            int64_t lo = 0, hi = n_targets;   /* is j a target? */
+            while (lo < hi) {
+                const int64_t mid = (lo + hi) / 2;
+                if (targets[mid] < j) lo = mid + 1; else hi = mid;
+            }
+            if (lo == n_targets || targets[lo] != j) continue;
+            const double a = 1.0 / sqrt((double)deg[i] * (double)deg[j]);
+            double* o = out + lo * F;
+            for (int64_t f = 0; f < F; ++f) o[f] += a * g[f];
         }
     }
 }

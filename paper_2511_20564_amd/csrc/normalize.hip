@@ -27,6 +27,10 @@ namespace e2eg {
 namespace {
 
 constexpr int kThreads = 256;
+// The symmetry test of unpack_columns keeps a flag (asym[0]) and a count spread over kSymCounters
+// addresses, one cache line each (asym[k * kSymStride], k = 1 .. kSymCounters).
+constexpr int kSymCounters = 64;
+constexpr int kSymStride = 32;
 constexpr int kLengthCutCost = 6;   // in quarters: an entry of a segment cut by length only weighs 1.5 entries in the deal
 
 // Per node: degree, d^-1/2, and the sort key (larger degree first, then node id): n - d in the
@@ -49,7 +53,7 @@ __global__ void mark_top(const uint64_t* __restrict__ sorted, int64_t n, int32_t
     if (p > n) return;
     if (p == n) {
         not_top[p] = 0;
-        *asym = 0;
+        for (int k = 0; k <= kSymCounters; ++k) asym[k * kSymStride] = 0;
         return;
     }
     const int32_t i = (int32_t)(uint32_t)sorted[p];
@@ -158,7 +162,9 @@ __global__ void emit_rows(RowScans sc, const int32_t* __restrict__ pair_off, int
         h.n_multi = sc.multi_off[n];
         h.n = (int32_t)n;
         h.nnz = (int32_t)nnz;
-        h.flags = *asym ? kSchedNotSymmetric : 0;
+        uint32_t balance = 0;   // looking minus not-looking entries (see unpack_columns), modulo 2^32
+        for (int k = 1; k <= kSymCounters; ++k) balance += (uint32_t)asym[k * kSymStride];
+        h.flags = (asym[0] != 0 || balance != 0) ? kSchedNotSymmetric : 0;
         h.pad = 0;
         for (int x = 0; x <= kXcds; ++x) h.xcd_first[x] = h.n_slot;  // lowered by deal_segments
         for (int x = 0; x < 7; ++x) h.pad2[x] = 0;
@@ -303,27 +309,47 @@ __global__ __launch_bounds__(kThreads) void entry_keys(const int32_t* __restrict
     keys[e] = ((uint64_t)(uint32_t)zpos[row] << bits) | (uint32_t)zpos[col_idx[e]];
 }
 
-// Sorted (row, column) keys -> the column array.  The same pass looks for the mirror image of every
-// entry (the key (column, row), by binary search in that row's stretch of the sorted keys): the
-// transposed entry points run on this schedule only if the structure is symmetric.
-__global__ void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, int bits,
-                               const int32_t* __restrict__ zrow_ptr, int32_t* __restrict__ zcol,
-                               int32_t* __restrict__ asym) {
+// Sorted (row, column) keys -> the column array.  The same pass decides whether the structure is
+// symmetric (the transposed entry points run on this schedule only if it is).  Of the two entries of
+// a symmetric pair exactly one "looks": the one whose own row is the longer (ties: the larger row id).
+// It searches for its mirror (column, row) in the other row's stretch of the sorted keys, which is
+// the shorter one, so no search walks a popular node's row.  The structure is symmetric iff every
+// looking entry finds its mirror and there are as many looking as not-looking entries (the mirrors
+// found are distinct not-looking entries; equal counts leave none without a partner).
+__global__ __launch_bounds__(kThreads) void unpack_columns(const uint64_t* __restrict__ keys, int64_t nnz, int bits,
+                                                           const int32_t* __restrict__ zrow_ptr,
+                                                           int32_t* __restrict__ zcol, int32_t* __restrict__ asym) {
+    __shared__ int32_t balance;
+    if (threadIdx.x == 0) balance = 0;
+    __syncthreads();
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= nnz) return;
-    const uint64_t key = keys[e];
-    const uint32_t c = (uint32_t)(key & ((1ull << bits) - 1));
-    const uint32_t r = (uint32_t)(key >> bits);
-    zcol[e] = (int32_t)c;
-    if (r == c) return;
-    const uint64_t mirror = ((uint64_t)c << bits) | r;
-    int32_t lo = zrow_ptr[c], hi = zrow_ptr[c + 1];   // first position with key >= mirror
-    const int32_t end = hi;
-    while (lo < hi) {
-        const int32_t mid = lo + ((hi - lo) >> 1);
-        if (keys[mid] < mirror) lo = mid + 1; else hi = mid;
+    int32_t mine = 0;   // +1 looking, -1 not looking, 0 diagonal / past the end
+    if (e < nnz) {
+        const uint64_t key = keys[e];
+        const uint32_t c = (uint32_t)(key & ((1ull << bits) - 1));
+        const uint32_t r = (uint32_t)(key >> bits);
+        zcol[e] = (int32_t)c;
+        if (r != c) {
+            const int32_t cb = zrow_ptr[c], ce = zrow_ptr[c + 1];
+            const int32_t own = zrow_ptr[r + 1] - zrow_ptr[r], other = ce - cb;
+            const bool looks = own > other || (own == other && r > c);
+            mine = looks ? 1 : -1;
+            if (looks) {
+                const uint64_t mirror = ((uint64_t)c << bits) | r;
+                int32_t lo = cb, hi = ce;   // first position with key >= mirror
+                while (lo < hi) {
+                    const int32_t mid = lo + ((hi - lo) >> 1);
+                    if (keys[mid] < mirror) lo = mid + 1; else hi = mid;
+                }
+                if (lo >= ce || keys[lo] != mirror) atomicOr(asym, 1);
+            }
+        }
     }
-    if (lo >= end || keys[lo] != mirror) atomicOr(asym, 1);
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_down(mine, off);
+    if ((threadIdx.x & 63) == 0 && mine != 0) atomicAdd(&balance, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && balance != 0)
+        atomicAdd(asym + (1 + blockIdx.x % kSymCounters) * kSymStride, balance);
 }
 
 // Weighted graphs.  d~_i = sum of the stored values of row i (the diagonal entry carries the 1 of
@@ -402,7 +428,7 @@ struct NormWs {
     int32_t* bounds;     // [wide rows][windows + 1]
     int32_t* pair_nseg;  // [wide rows * windows + 1]
     uint64_t* seg_len;   // [max_seg + 1]
-    int32_t* asym;       // [1] raised when the structure is not symmetric
+    int32_t* asym;       // symmetry flag and spread counters (see unpack_columns)
     Segment* seg_tmp;
     void* scan_ws;
     void* sort_ws;
@@ -427,7 +453,7 @@ NormWs carve_norm(void* base, int64_t n, int64_t nnz) {
     w.bounds = c.take<int32_t>(sched_max_wide_rows(n) * (sched_windows(n) + 1) + 1);
     w.pair_nseg = c.take<int32_t>(sched_max_pairs(n) + 1);
     w.seg_len = c.take<uint64_t>(max_seg + 1);
-    w.asym = c.take<int32_t>(1);
+    w.asym = c.take<int32_t>((kSymCounters + 1) * kSymStride);
     w.seg_tmp = c.take<Segment>(max_seg);
     w.scan_ws = c.take<char>(5 * scan_workspace_bytes(m));   // the five row scans share one set of launches
     w.sort_ws = c.take<char>(radix_sort_workspace_bytes(m));

@@ -375,7 +375,6 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
 constexpr int kShortPerWave = 8;   // short rows a wavefront works through, 64/G at a time
-constexpr int kSegBlocksPerXcd = 2048;    // most A-workgroups per XCD
 constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when the graph cannot have that many such rows)
 
 // Three kinds of workgroup.
@@ -383,8 +382,13 @@ constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when th
 //    ordered by first column), one per wavefront.  The schedule deals the list out to the XCDs in
 //    contiguous stretches of equal entry counts; the A-workgroups of XCD x take the segments of
 //    stretch x in order, so the segments in flight on an XCD are consecutive ones, read the same
-//    window of feature rows, and share it in that XCD's L2.  (Should a stretch be longer than
-//    the launch was sized for, the workgroups go round again.)
+//    window of feature rows, and share it in that XCD's L2.  The launch is sized so that each
+//    wavefront takes one segment, which keeps the segments in flight on an XCD next to each other in
+//    the list (a stretch longer than the launch was sized for goes round again).  (Measured on the 50 M-edge
+//    graph: with the A-workgroups capped at 2048 per XCD and going round their stretch three times,
+//    three distant stretches of windows were in flight at once and the kernel fetched 12.0 GB per
+//    launch instead of 10.7; the empty workgroups of the uncapped launch leave at once and cost
+//    nothing measurable.)
 // B. Rows of one segment, in row order; a fixed number of workgroups with equal shares.
 // C. Short rows, kShortPerWave consecutive entries of the ordered short-row list per wavefront.
 //    The wavefront fetches row numbers, bounds, node ids and scales of all its rows up front
@@ -609,10 +613,10 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     const uint64_t row_bytes = (uint64_t)a.F * sizeof(typename T::elem);
     const uint64_t table_bytes = (uint64_t)(n + 1) * row_bytes;
     const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
-    // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs
-    // (capped: the A-workgroups go round their stretch again, and unused workgroups still cost a dispatch)
+    // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs.  The bound
+    // on slotted segments is about three times what a graph really has, so an eighth of it per XCD
+    // covers every stretch the deal by entry counts produces in practice; a longer one goes round again.
     int64_t a_blocks = nnz > kSegLen ? ceil_div(ceil_div(sched_max_slot(n, nnz), kWaves), kXcds) + 1 : 0;
-    if (a_blocks > kSegBlocksPerXcd) a_blocks = kSegBlocksPerXcd;
     int64_t b_blocks = nnz > kShortMax ? ceil_div(ceil_div(sched_max_plain(nnz), kWaves), kXcds) + 1 : 0;
     if (b_blocks > kSingleBlocksPerXcd) b_blocks = kSingleBlocksPerXcd;
     const int64_t c_blocks = ceil_div(ceil_div(n, kWaves * kShortPerWave), kXcds) + 1;

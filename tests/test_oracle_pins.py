@@ -94,6 +94,54 @@ def test_csr_structure_config1(oracle):
     assert all((c_, r_) in fwd for r_, c_ in fwd)
 
 
+@pytest.mark.parametrize("self_loops", [True, False])
+def test_csr_by_row_ranges_is_the_csr(oracle, self_loops):
+    """Building the structure range by range gives the rows of the whole structure (and of the dense
+    pattern), for ranges inside the users, inside the items, across both, empty and whole."""
+    nu, ni, u, i = small_graph(9, nu=17, ni=11, ne=60)
+    n = nu + ni
+    row_ptr, col = oracle.build_csr(nu, ni, u, i, add_self_loops=self_loops)
+    _, At = dense_ahat(nu, ni, u, i, self_loops)
+    for lo, hi in [(0, n), (0, 5), (5, nu), (nu - 3, nu + 4), (nu, n), (n - 1, n), (7, 7)]:
+        rp, cl = oracle.build_csr_rows(nu, ni, u, i, lo, hi, add_self_loops=self_loops)
+        assert rp[0] == 0 and np.array_equal(rp, row_ptr[lo:hi + 1] - row_ptr[lo])
+        assert np.array_equal(cl, col[row_ptr[lo]:row_ptr[hi]])
+        for r in range(lo, hi):
+            assert np.array_equal(cl[rp[r - lo]:rp[r - lo + 1]], np.flatnonzero(At[r] > 0))
+    with pytest.raises(ValueError):
+        oracle.build_csr_rows(nu, ni, u, i, 3, n + 1)
+
+
+def test_transposed_rows_to_targets_is_the_dense_transpose(oracle):
+    """The backward restricted to target nodes, built up over row ranges, equals rows of A^T G of the
+    dense operator -- on a symmetric structure and on one that is not."""
+    nu, ni, u, i = small_graph(31, nu=12, ni=10, ne=50)
+    n = nu + ni
+    Ahat, _ = dense_ahat(nu, ni, u, i)
+    row_ptr, col = oracle.build_csr(nu, ni, u, i)
+    rng = np.random.default_rng(2)
+    G = rng.standard_normal((n, 4))
+    targets = np.array([0, 3, nu - 1, nu, nu + 4, n - 1])
+    out = np.zeros((targets.size, 4))
+    for lo, hi in [(0, 7), (7, nu + 2), (nu + 2, n)]:
+        rp, cl = oracle.build_csr_rows(nu, ni, u, i, lo, hi)
+        oracle.transposed_to_targets(lo, rp, cl, np.diff(row_ptr), G, targets, out)
+    assert relerr(out, (Ahat.T @ G)[targets]) < 1e-13
+    # a structure that is not symmetric: the rows of M^T G, not of M G
+    row_ptr = np.array([0, 2, 3, 4, 7], dtype=np.int64)
+    col = np.array([1, 3, 0, 3, 0, 1, 2], dtype=np.int32)
+    length = np.diff(row_ptr)
+    M = np.zeros((4, 4))
+    for r in range(4):
+        for p in range(row_ptr[r], row_ptr[r + 1]):
+            M[r, col[p]] = 1.0 / np.sqrt(length[r] * length[col[p]])
+    G = rng.standard_normal((4, 3))
+    out = np.zeros((3, 3))
+    oracle.transposed_to_targets(0, row_ptr[:3], col[:row_ptr[2]], length, G, np.array([0, 1, 3]), out)
+    oracle.transposed_to_targets(2, row_ptr[2:] - row_ptr[2], col[row_ptr[2]:], length, G, np.array([0, 1, 3]), out)
+    assert relerr(out, (M.T @ G)[[0, 1, 3]]) < 1e-13 and relerr(out, (M @ G)[[0, 1, 3]]) > 1e-2
+
+
 def test_build_csr_rejects_bad_ids(oracle):
     with pytest.raises(ValueError):
         oracle.build_csr(3, 2, np.array([0, 3]), np.array([0, 1]))
