@@ -196,6 +196,24 @@ int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
                              const void* d_gH, void* d_gP, float* d_gW, void* ws,
                              size_t ws_bytes, void* stream);
 
+/* e2eg_layer_transform_noalloc: e2eg_layer_transform, argument for argument, without (ws, ws_bytes),
+ * for callers that cannot allocate device memory or pass a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The partial weight-gradient
+ * matrices of the backward mode go to a static device array inside the library instead, of
+ * E2EG_TRANSFORM_STATIC_SCRATCH_BYTES (16 MiB) on every GPU the library runs on, held until the
+ * process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ * Limit: e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype) must not exceed that size
+ * (128 x 128 weights: any n; 256 x 256: n up to 8192), else E2EG_ERR_CAPACITY and nothing is
+ * enqueued.  Results are those of e2eg_layer_transform bit for bit (same kernels, same order).
+ * All calls on one GPU share the one array: two calls whose kernels may overlap on that GPU (different
+ * streams, or threads) race on it; calls on one stream are ordered and safe.  The first call on each
+ * device looks up the array's address and should be made outside graph capture.
+ */
+#define E2EG_TRANSFORM_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t e2eg_layer_transform_noalloc(int32_t mode, int32_t n, int32_t Fin, int32_t Fout, int32_t dtype,
+                                     int32_t relu, const void* d_P, const void* d_W, void* d_H,
+                                     const void* d_gH, void* d_gP, float* d_gW, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * e2eg_readout_mean: layer combination of LightGCN (Section 3.1): the final representation is
  * the mean of all layers,  Y = 1/(K+1) * (H(0) + H(1) + ... + H(K)).

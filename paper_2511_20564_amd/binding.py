@@ -44,6 +44,7 @@ SIGNATURES = {
     "e2eg_propagate_bwd": (_i32, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_layer_transform_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "e2eg_layer_transform": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "e2eg_layer_transform_noalloc": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "e2eg_aggregate_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
     "e2eg_aggregate": (_i32, [_i32, _i32, _i64, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "e2eg_readout_mean": (_i32, [_i32, _i32, _i32, _i32, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
@@ -277,6 +278,11 @@ def e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d
     _check(load_library().e2eg_layer_transform(mode, n, Fin, Fout, dtype, relu, _ptr(d_P), _ptr(d_W), _ptr(d_H),
                                                _ptr(d_gH), _ptr(d_gP), _ptr(d_gW), _ptr(ws),
                                                _nbytes(ws) if ws_bytes is None else ws_bytes, stream or None))
+
+
+def e2eg_layer_transform_noalloc(mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d_gP, d_gW, stream=0):
+    _check(load_library().e2eg_layer_transform_noalloc(mode, n, Fin, Fout, dtype, relu, _ptr(d_P), _ptr(d_W),
+                                                       _ptr(d_H), _ptr(d_gH), _ptr(d_gP), _ptr(d_gW), stream or None))
 
 
 def e2eg_profile_begin(capacity: int):

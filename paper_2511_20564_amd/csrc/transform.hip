@@ -14,6 +14,8 @@
 //             (no atomics, reproducible).
 #include "common.h"
 
+#include <mutex>
+
 namespace e2eg {
 namespace {
 
@@ -364,11 +366,41 @@ extern "C" size_t e2eg_layer_transform_workspace_bytes(int32_t mode, int32_t n, 
     return align_up((size_t)blocks * (size_t)Fin * (size_t)Fout * sizeof(float));
 }
 
-extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
-                                        int32_t dtype, int32_t relu, const void* d_P,
-                                        const void* d_W, void* d_H, const void* d_gH, void* d_gP,
-                                        float* d_gW, void* ws, size_t ws_bytes, void* stream_) {
-    const char* who = "layer_transform";
+// ---- the same call for callers that cannot allocate ------------------------------------------
+// The partial weight-gradient matrices live in a device array that is part of the library's code
+// object, so no workspace has to come from anywhere.  Each GPU holds its own copy of the array at
+// its own address; host code never uses the array's name as an address, only the pointer
+// hipGetSymbolAddress returns for the current device, looked up once per device and kept.
+static __device__ __align__(256) float scratch[E2EG_TRANSFORM_STATIC_SCRATCH_BYTES / sizeof(float)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices];   // address of `scratch` on each device, null until looked up
+
+int32_t static_scratch_of_current_device(float** out) {
+    int dev = -1;
+    E2EG_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(E2EG_ERR_HIP, "layer_transform_noalloc: device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float* p = nullptr;
+        E2EG_HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+        if (!p) return fail(E2EG_ERR_HIP, "layer_transform_noalloc: the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return E2EG_OK;
+}
+}  // namespace
+
+namespace {
+// Shared by the two entry points: `ws` is the caller's workspace, or the library's static scratch
+// array (static_scratch: looked up here once the arguments have passed; a need beyond its size is a
+// CAPACITY error).
+int32_t transform_impl(const char* who, bool static_scratch, int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
+                       int32_t dtype, int32_t relu, const void* d_P, const void* d_W, void* d_H, const void* d_gH,
+                       void* d_gP, float* d_gW, void* ws, size_t ws_bytes, void* stream_) {
     if (mode != E2EG_TRANSFORM_FWD && mode != E2EG_TRANSFORM_BWD)
         return fail(E2EG_ERR_INVALID_ARG, "%s: mode %d", who, mode);
     if (dtype != E2EG_BF16)
@@ -383,6 +415,17 @@ extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, in
     for (const void* q : ptrs)
         if (q && !aligned_to(q, 16)) return fail(E2EG_ERR_INVALID_ARG, "%s: a pointer is not 16-byte aligned", who);
     const size_t need = e2eg_layer_transform_workspace_bytes(mode, n, Fin, Fout, dtype);
+    if (static_scratch && E2EG_TRANSFORM_STATIC_SCRATCH_BYTES < need)
+        return fail(E2EG_ERR_CAPACITY, "%s: n=%d, Fin=%d, Fout=%d need %zu bytes of scratch memory, the static array "
+                                       "holds %zu; use e2eg_layer_transform with a workspace", who, n, Fin, Fout, need,
+                    (size_t)E2EG_TRANSFORM_STATIC_SCRATCH_BYTES);
+    if (static_scratch) {   // arguments are fine: now the array's address on this device
+        float* ptr = nullptr;
+        const int32_t st = static_scratch_of_current_device(&ptr);
+        if (st != E2EG_OK) return st;
+        ws = ptr;
+        ws_bytes = E2EG_TRANSFORM_STATIC_SCRATCH_BYTES;
+    }
     if (!ws || !aligned_to(ws, kAlign) || ws_bytes < need)
         return fail(E2EG_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -417,4 +460,22 @@ extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, in
         E2EG_LAUNCH_CHECK("weight_grad_reduce");
     }
     return E2EG_OK;
+}
+}  // namespace
+
+extern "C" int32_t e2eg_layer_transform(int32_t mode, int32_t n, int32_t Fin, int32_t Fout,
+                                        int32_t dtype, int32_t relu, const void* d_P,
+                                        const void* d_W, void* d_H, const void* d_gH, void* d_gP,
+                                        float* d_gW, void* ws, size_t ws_bytes, void* stream) {
+    return transform_impl("layer_transform", false, mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d_gP, d_gW, ws,
+                          ws_bytes, stream);
+}
+
+extern "C" int32_t e2eg_layer_transform_noalloc(int32_t mode, int32_t n, int32_t Fin, int32_t Fout, int32_t dtype,
+                                                int32_t relu, const void* d_P, const void* d_W, void* d_H,
+                                                const void* d_gH, void* d_gP, float* d_gW, void* stream) {
+    // every partial matrix the reduction reads is written in full by the kernel before it, so the
+    // array's old contents (the previous call's) never show and nothing has to be cleared
+    return transform_impl("layer_transform_noalloc", true, mode, n, Fin, Fout, dtype, relu, d_P, d_W, d_H, d_gH, d_gP,
+                          d_gW, nullptr, 0, stream);
 }

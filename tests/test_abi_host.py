@@ -295,3 +295,19 @@ def test_device_helpers_refuse_to_run_without_gpu():
     import paper_2511_20564_amd.device as dev
     with pytest.raises(RuntimeError):
         dev.propagate_fwd(None, torch.zeros(4, 4), 1)
+
+
+def test_noalloc_transform_checks_arguments_before_it_touches_the_device(B):
+    f = B.e2eg_layer_transform_noalloc
+    fwd, bwd = B.E2EG_TRANSFORM_FWD, B.E2EG_TRANSFORM_BWD
+    assert status_of(B, f, 7, 10, 128, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, None, None) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, fwd, 10, 128, 128, B.E2EG_F32, 1, FAKE, FAKE, FAKE, None, None, None) == B.E2EG_ERR_BAD_DTYPE
+    assert status_of(B, f, fwd, 10, 100, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, None, None) == B.E2EG_ERR_INVALID_ARG
+    assert status_of(B, f, fwd, 10, 128, 128, B.E2EG_BF16, 1, None, FAKE, FAKE, None, None, None) == B.E2EG_ERR_NULL_PTR
+    assert status_of(B, f, bwd, 10, 128, 128, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, None, FAKE, FAKE) == B.E2EG_ERR_NULL_PTR
+    # more partial matrices than the static array holds: refused on the host, nothing enqueued
+    assert B.e2eg_layer_transform_workspace_bytes(bwd, 100_000, 256, 256, B.E2EG_BF16) > 16 << 20
+    assert status_of(B, f, bwd, 100_000, 256, 256, B.E2EG_BF16, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE) == B.E2EG_ERR_CAPACITY
+    assert "static array" in B.e2eg_last_error()
+    # any n fits with 128 x 128 weights
+    assert B.e2eg_layer_transform_workspace_bytes(bwd, 2_000_000_000, 128, 128, B.E2EG_BF16) <= 16 << 20
