@@ -21,8 +21,12 @@
  *     call returns without waiting, except e2eg_build_csr, which waits once to return nnz.
  *   - Feature matrices are row-major [n][F] with a leading dimension (in elements) >= F.
  *     dtype E2EG_F32: float.  dtype E2EG_BF16: bfloat16 bit patterns (uint16); arithmetic is
- *     fp32 and each stored layer is rounded to nearest-even once.  F must be a multiple of 4
- *     (fp32) or 8 (bf16), leading dimensions too, and base pointers 16-byte aligned.
+ *     fp32 and each stored layer is the fp32 result rounded to nearest-even once.  Between the
+ *     layers of one call the next layer's input is kept in the workspace as d~^-1/2 H(l) in the
+ *     storage type: the same fp32 result, scaled, with a rounding of its own (not the stored H(l)
+ *     re-read), so a K-layer call and K one-layer calls agree to rounding, not bit for bit.
+ *     F must be a multiple of 4 (fp32) or 8 (bf16), leading dimensions too, and base pointers
+ *     16-byte aligned.
  *   - Return value: E2EG_OK or a negative E2EG_ERR_* code; e2eg_last_error() gives a
  *     thread-local message for the last failure on the calling thread.  Argument errors are
  *     found on the host before anything is enqueued.  No C++ exception crosses this boundary.

@@ -207,16 +207,16 @@ def build_csr_rows(n_users, n_items, users, items, row_lo, row_hi, add_self_loop
     if rows < 0:
         raise ValueError("empty or reversed row range")
     row_ptr = np.zeros(rows + 1, dtype=np.int64)
-    col = np.empty(0, dtype=np.int32)
-    for _ in range(2):          # first call sizes the column array, second fills it
-        nnz = _load().e2eg_oracle_build_csr_rows(n_users, n_items, users.size, _p(users, _i32p), _p(items, _i32p),
-                                                 1 if add_self_loops else 0, int(row_lo), int(row_hi),
-                                                 _p(row_ptr, _i64p), _p(col, _i32p), col.size)
-        if nnz < 0:
-            raise ValueError("bad row range, user or item id out of range, or out of memory")
-        if nnz <= col.size:
-            break
-        col = np.empty(nnz, dtype=np.int32)
+    # room for every listed entry of the range (repeated pairs make the result shorter)
+    listed = (int(np.count_nonzero((users >= row_lo) & (users < row_hi)))
+              + int(np.count_nonzero((items >= row_lo - n_users) & (items < row_hi - n_users)))
+              + (rows if add_self_loops else 0))
+    col = np.empty(max(listed, 1), dtype=np.int32)
+    nnz = _load().e2eg_oracle_build_csr_rows(n_users, n_items, users.size, _p(users, _i32p), _p(items, _i32p),
+                                             1 if add_self_loops else 0, int(row_lo), int(row_hi),
+                                             _p(row_ptr, _i64p), _p(col, _i32p), col.size)
+    if nnz < 0 or nnz > col.size:
+        raise ValueError("bad row range, user or item id out of range, or out of memory")
     return row_ptr, col[:nnz]
 
 

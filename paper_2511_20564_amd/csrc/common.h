@@ -148,6 +148,8 @@ struct SchedView {
     int32_t* slot_cnt;    // [max_multi] number of slots
     Segment* segs;        // [max_seg]: slotted segments ordered by first column, then one-segment rows
     float* zval;          // [nnz] entry values in zcol order (weighted schedules only, else null)
+    int32_t* znode;       // [nnz] orig[zcol[e]]: the column of entry e as a node id
+    float* zs;            // [nnz] d~^-1/2 of that node (times the entry's value on a weighted graph)
     int64_t max_plain, max_seg, max_multi, max_slot;
 };
 

@@ -410,6 +410,17 @@ __global__ __launch_bounds__(kThreads) void place_values(const int32_t* __restri
         atomicOr(&s.header->flags, kSchedValuesNotSymmetric);
 }
 
+// One thread per entry of the internal CSR: its column as a node id and that node's d~^-1/2 (times
+// the entry's value on a weighted graph).  The first layer of a propagation reads these beside each
+// other and gathers the caller's feature rows directly, which saves the pass that would pre-scale them.
+__global__ void entry_scales(SchedView s, const float* __restrict__ dinv_sqrt, int64_t nnz) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t node = s.orig[s.zcol[e]];
+    s.znode[e] = node;
+    s.zs[e] = s.zval ? s.zval[e] * dinv_sqrt[node] : dinv_sqrt[node];
+}
+
 __global__ void zero_values(float* __restrict__ v, int64_t count) {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e < count) v[e] = 0.0f;
@@ -601,6 +612,11 @@ int32_t normalize_impl(int32_t n, int64_t nnz, const int32_t* d_row_ptr, const i
             place_values<<<grid_for(nnz), blk, 0, stream>>>(d_row_ptr, d_col_idx, d_val, n, nnz, view);
             E2EG_LAUNCH_CHECK("place_values");
         }
+    }
+    // 5. per entry: column as a node id, and the scale the first layer multiplies its row by
+    if (nnz > 0) {
+        entry_scales<<<grid_for(nnz), blk, 0, stream>>>(view, d_dinv_sqrt, nnz);
+        E2EG_LAUNCH_CHECK("entry_scales");
     }
     return E2EG_OK;
 }

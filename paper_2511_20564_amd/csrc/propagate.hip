@@ -4,12 +4,17 @@
 //
 // How the GPU evaluates it.  With s = d~^-1/2 and Z(l) = S H(l) (rows pre-scaled by s),
 //     H(l+1) = S * (A~ Z(l)),        Z(l+1) = S * H(l+1),
-// so a layer is an UNWEIGHTED sum of neighbour rows of Z followed by one scale per output row:
-// the only per-edge datum read is the 4-byte column index.  Z(0) is made by one streaming
-// pre-scale pass; every later Z(l) is written by the layer that produces it.  Layers the caller
-// asked for are stored as H(l); layers it did not ask for exist only as Z(l).  Every Z buffer
-// carries one extra all-zero row (index n): "no neighbour" lanes read it, which keeps the
-// gather loop free of per-lane predicates.
+// so a layer is an UNWEIGHTED sum of neighbour rows of Z followed by one scale per output row: the
+// only per-edge datum read is the 4-byte column index.  Z(0) is made by one streaming pre-scale
+// pass; every later Z(l) is written by the layer that produces it.  Layers the caller asked for are
+// stored as H(l); layers it did not ask for exist only as Z(l).  Every Z buffer carries one extra
+// all-zero row (index n): "no neighbour" lanes read it, which keeps the gather loop free of
+// per-lane predicates.
+// Where the pre-scale pass would cost as much as the work it prepares (a single-layer call, a
+// small graph) the first layer instead gathers the caller's rows H(0) directly, by node id, and
+// multiplies each by s_j, both read from the schedule beside each other (kFirst below; a lane
+// without a neighbour then gathers its row's first neighbour again with weight 0, the caller's table
+// having no zero row).
 //
 // Kernel shape (wave64).  The kernels read the renumbered copy of the graph that e2eg_normalize
 // leaves in the schedule ("internal" ids, see common.h); Z buffers are in internal row order, H
@@ -28,10 +33,12 @@
 //     on a power-law graph most rows are short and this per-row work, not memory, was what bound
 //     the first version of the kernel (vector-ALU issue).
 // On a weighted graph (e2eg_propagate_weighted_*) the schedule also holds the entries' values, in
-// the order of its own column indices; the WEIGHTED instantiation of the kernel loads them beside
-// the indices (same predicates), hands them to the lanes by the same shuffles, and replaces the
-// add of a gathered row by a multiply-add.  e2eg_aggregate is the same kernel with other per-row
-// scales (mean, transposed mean, plain sum) and an optional addend.
+// the order of its own column indices; the instantiations that carry a value per entry (kValues:
+// inner layers of a weighted graph; kFirst: the first layer of any graph) load it beside the
+// index (same predicates), hand it to the lanes by the same shuffles, and replace the add of a
+// gathered row by a multiply-add.  e2eg_aggregate is the kernel of the inner layers on a table
+// pre-scaled by a streaming pass, with other per-row scales (mean, transposed mean, plain sum) and
+// an optional addend.
 // Measured on gfx950: the dot-product instruction v_dot2c_f32_bf16 with unit weights adds a
 // bf16 pair in one instruction instead of shift + add per element, but ran slower than the plain
 // sequence, and capping registers for more resident wavefronts cost more in spills than it gained;
@@ -116,7 +123,11 @@ template <typename T>
 struct LayerArgs {
     const float* dinv_sqrt;       // by node id
     SchedView sched;              // internal graph (see common.h)
-    const typename T::elem* zin;  // Z(l) = S H(l), [n + 1][F] in internal order, row n all zero
+    const typename T::elem* zin;  // Z(l) = S H(l), [n + 1][F] in internal order, row n all zero; kFirst: H(0) by node id
+    int64_t ld_in;                // leading dimension of zin in elements (F for a Z buffer)
+    const int32_t* cols;          // column of every entry: zcol (rows of Z), or znode for kFirst
+    const float* vals;            // value of every entry: null (kPlain), zval (kValues), zs (kFirst)
+    int32_t transposed;           // the call computes with the transpose of the stored operator
     typename T::elem* out_h;      // H(l+1) by node id, or null
     int64_t ld_h;
     typename T::elem* out_z;      // Z(l+1) = S H(l+1), [n + 1][F] in internal order, or null
@@ -128,6 +139,24 @@ struct LayerArgs {
     int32_t a_blocks;             // workgroups per XCD the launch provides for slotted segments
     int32_t b_blocks;             // workgroups per XCD for rows of one segment
 };
+
+// What a gathered row is multiplied by: nothing (inner layers), the entry's value (inner layers of a
+// weighted graph), or s_j times that value while the rows come from the caller's H(0) (first layer).
+constexpr int kPlain = 0, kValues = 1, kFirst = 2;
+
+// The backward entry points apply the stored operator itself, which is its transpose only if structure
+// and values are symmetric; a schedule that e2eg_normalize found not to be is refused on the device,
+// without a read-back: every row scale, and so every result, is NaN.  Decided once per wavefront, at
+// the start of the kernel (a scalar load inside the row loops would wait for the cross-lane moves in
+// flight with it).
+template <typename T>
+__device__ __forceinline__ bool refused(const LayerArgs<T>& a) {
+    return a.transposed && a.sched.header->flags != 0;
+}
+template <typename T>
+__device__ __forceinline__ float row_scale(const LayerArgs<T>& a, int32_t node, bool refuse) {
+    return refuse ? __builtin_nanf("") : a.dinv_sqrt[node];
+}
 
 // Accumulators of one lane: acc[v] holds this lane's 16-byte chunk as fp32.
 template <typename T>
@@ -173,6 +202,7 @@ struct Sum {
         for (int u = 0; u < U; ++u)
             if (u < live) add_scaled(q[u], w[u]);
     }
+
     // -> out[] = the chunk's total over the lane groups, valid in lanes of group 0
     template <int LOG_G>
     __device__ __forceinline__ void total(float (&out)[T::kVec]) {
@@ -221,32 +251,43 @@ __device__ __forceinline__ uint4 gather16(const LayerArgs<T>& a, int32_t j, uint
 }
 
 constexpr int kInFlight = 8;  // independent 16-byte gathers in flight per lane
+// The column indices (and entry values) are streamed once, but they are read with ordinary loads:
+// measured, non-temporal loads for them cost 6 % (500 M-edge graph, 128-byte rows) to 9 % (2 M-edge
+// fp32 graph) of a launch.
 
 // One segment (entries [beg, end) of internal row seg.row, at most kSegLen of them), all 64 lanes
 // on the one row: G lanes per neighbour row, 64/G neighbour rows per load instruction.  Column
 // indices are fetched 64 at a time, one coalesced load, the next 64 requested before the current
 // gathers are consumed.  slot >= 0: the sum goes to that partial-sum slot; slot < 0: the segment is
 // the whole row and the row is finished here.
-template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
-__device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment seg, const int lane) {
+template <typename T, int LOG_G, bool NARROW, int MODE>
+__device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment seg, const int lane,
+                                            const bool refuse) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
     constexpr int V = T::kVec;
     constexpr int U = kInFlight;
+    constexpr bool VALS = MODE != kPlain;
     const int g = lane >> LOG_G;
     const int c = lane & (G - 1);
     const int chunks = a.F / V;
-    const uint32_t row_bytes = (uint32_t)a.F * (uint32_t)sizeof(typename T::elem);
+    const uint32_t row_bytes = (uint32_t)a.ld_in * (uint32_t)sizeof(typename T::elem);
     int32_t node = 0;
     float s = 0.0f;
     if (seg.slot < 0) {  // requested now, needed after the gathers
         node = a.sched.orig[seg.row];
-        s = a.dinv_sqrt[node];
+        s = row_scale<T>(a, node, refuse);
     }
-    const int32_t idx_first = lane < seg.end - seg.beg ? __builtin_nontemporal_load(a.sched.zcol + seg.beg + lane) : a.n;
-    float wgt_first = 0.0f;  // WEIGHTED: the entries' values travel with their column indices
-    if constexpr (WEIGHTED)
-        if (lane < seg.end - seg.beg) wgt_first = __builtin_nontemporal_load(a.sched.zval + seg.beg + lane);
+    // What a lane without a neighbour gathers: the all-zero row of a Z buffer; kFirst, whose table has
+    // no such row: the segment's own first neighbour, with weight 0 (adds 0, and NaN only where that
+    // neighbour makes the sum NaN anyway).
+    int32_t idx_first = lane < seg.end - seg.beg ? *(a.cols + seg.beg + lane) : a.n;
+    const int32_t none = MODE == kFirst ? __builtin_amdgcn_readfirstlane(idx_first) : a.n;
+    if constexpr (MODE == kFirst)
+        if (lane >= seg.end - seg.beg) idx_first = none;
+    float wgt_first = 0.0f;  // VALS: the entries' values travel with their column indices
+    if constexpr (VALS)
+        if (lane < seg.end - seg.beg) wgt_first = *(a.vals + seg.beg + lane);
 
     for (int cb = 0; cb < chunks; cb += G) {   // more than one pass only for rows wider than 1 KiB
         const int cc = cb + c;
@@ -258,28 +299,28 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
         float wgt = wgt_first;
         for (int32_t base = seg.beg; base < seg.end; base += 64) {
             const int cnt = seg.end - base < 64 ? seg.end - base : 64;
-            int32_t idx_next = a.n;
+            int32_t idx_next = none;
             float wgt_next = 0.0f;
             if (base + 64 < seg.end && lane < seg.end - base - 64) {
-                idx_next = __builtin_nontemporal_load(a.sched.zcol + base + 64 + lane);
-                if constexpr (WEIGHTED) wgt_next = __builtin_nontemporal_load(a.sched.zval + base + 64 + lane);
+                idx_next = *(a.cols + base + 64 + lane);
+                if constexpr (VALS) wgt_next = *(a.vals + base + 64 + lane);
             }
             int t = 0;
-            for (; t + U * NB <= cnt; t += U * NB) {   // full batches; lanes past the end hold the zero row
+            for (; t + U * NB <= cnt; t += U * NB) {   // full batches: every lane has a neighbour
                 uint4 q[U];
                 float wq[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
-                    if constexpr (WEIGHTED) wq[u] = __shfl(wgt, t + u * NB + g);
+                    if constexpr (VALS) wq[u] = __shfl(wgt, t + u * NB + g);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if constexpr (WEIGHTED) sum.add_scaled(q[u], wq[u]);
+                    if constexpr (VALS) sum.add_scaled(q[u], wq[u]);
                     else sum.add(q[u]);
                 }
             }
-            if (t < cnt) {
+            if (t < cnt) {   // lanes past the end hold `none`
                 const int live = (cnt - t + NB - 1) / NB;
                 uint4 q[U];
                 float wq[U];
@@ -287,9 +328,9 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
                 for (int u = 0; u < U; ++u)
                     if (u < live) {
                         q[u] = gather16<T, NARROW>(a, __shfl(idx, t + u * NB + g), row_bytes, lane_off);
-                        if constexpr (WEIGHTED) wq[u] = __shfl(wgt, t + u * NB + g);
+                        if constexpr (VALS) wq[u] = __shfl(wgt, t + u * NB + g);
                     }
-                if constexpr (WEIGHTED) sum.template add_batch_scaled<U>(q, wq, live);
+                if constexpr (VALS) sum.template add_batch_scaled<U>(q, wq, live);
                 else sum.template add_batch<U>(q, live);
             }
             idx = idx_next;
@@ -315,20 +356,28 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
 // NB = 64/G short rows side by side, lane group g on row g: no sum across lanes is needed and
 // every per-row step (bounds, scale, store) is paid once per NB rows.  Each lane group fetches G
 // of its row's column indices per load (one per lane) and hands them round with cross-lane
-// moves; groups whose row has ended gather the zero row.  `beg`, `len`, `zrow`, `node`, `s` are
-// per-lane values, equal within a lane group; len < 0 for a group without a row (an empty row,
-// len = 0, still gets its all-zero result stored).
-template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
+// moves; groups whose row has ended gather the zero row (kFirst, whose table has none: their row's
+// first neighbour again, with weight 0).  `beg`, `len`, `zrow`, `node`, `s` are per-lane values, equal
+// within a lane group; len < 0 for a group without a row (an empty row, len = 0, still gets its
+// all-zero result stored).
+template <typename T, int LOG_G, bool NARROW, int MODE>
 __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int32_t beg, const int32_t len,
                                                const int32_t zrow, const int32_t node, const float s,
                                                const int32_t idx_first, const float wgt_first, const int lane) {
     constexpr int G = 1 << LOG_G;
     constexpr int V = T::kVec;
     constexpr int U = kInFlight < G ? kInFlight : G;
+    constexpr bool VALS = MODE != kPlain;
     const int c = lane & (G - 1);
     const int group_base = lane & ~(G - 1);
     const int chunks = a.F / V;
-    const uint32_t row_bytes = (uint32_t)a.F * (uint32_t)sizeof(typename T::elem);
+    const uint32_t row_bytes = (uint32_t)a.ld_in * (uint32_t)sizeof(typename T::elem);
+    int32_t none = a.n;
+    if constexpr (MODE == kFirst) {   // lane 0 of the group holds the row's first neighbour (row 0 for an empty row)
+        none = __shfl(idx_first, group_base);
+        if (len <= 0) none = 0;
+    }
+    const int32_t idx_start = (MODE == kFirst && c >= len) ? none : idx_first;
     int maxlen = len;  // longest row of the batch (wave-uniform)
 #pragma unroll
     for (int off = G; off < 64; off <<= 1) {
@@ -343,14 +392,14 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
         const uint32_t lane_off = active ? (uint32_t)cc * 16u : 0u;
         Sum<T> sum;
         sum.clear();
-        int32_t idx = idx_first;
+        int32_t idx = idx_start;
         float wgt = wgt_first;
         for (int base = 0; base < maxlen; base += G) {
-            int32_t idx_next = a.n;
+            int32_t idx_next = none;
             float wgt_next = 0.0f;
             if (base + G + c < len) {
-                idx_next = __builtin_nontemporal_load(a.sched.zcol + beg + base + G + c);
-                if constexpr (WEIGHTED) wgt_next = __builtin_nontemporal_load(a.sched.zval + beg + base + G + c);
+                idx_next = *(a.cols + beg + base + G + c);
+                if constexpr (VALS) wgt_next = *(a.vals + beg + base + G + c);
             }
             const int steps = maxlen - base < G ? maxlen - base : G;
             for (int t = 0; t < steps; t += U) {
@@ -361,14 +410,16 @@ __device__ __forceinline__ void run_short_rows(const LayerArgs<T>& a, const int3
                 for (int u = 0; u < U; ++u)
                     if (u < live) {
                         q[u] = gather16<T, NARROW>(a, __shfl(idx, group_base + t + u), row_bytes, lane_off);
-                        if constexpr (WEIGHTED) wq[u] = __shfl(wgt, group_base + t + u);
+                        if constexpr (VALS) wq[u] = __shfl(wgt, group_base + t + u);
                     }
-                if constexpr (WEIGHTED) sum.template add_batch_scaled<U>(q, wq, live);
+                if constexpr (VALS) sum.template add_batch_scaled<U>(q, wq, live);
                 else sum.template add_batch<U>(q, live);
             }
             idx = idx_next;
             wgt = wgt_next;
         }
+        if constexpr (MODE == kFirst)
+            if (len == 0) sum.clear();   // an empty row gathered row 0 with weight 0: its sum is 0 whatever row 0 holds
         if (active && len >= 0) finish_vec<T>(a, zrow, node, s, cc * V, sum.acc);
     }
 }
@@ -400,13 +451,26 @@ constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when th
 // workgroups beyond the real ones, all at the end of each XCD's sequence, leave at once.
 // (Measured: spreading the L2-bound A-workgroups evenly among the HBM-bound others, so that both
 // resources are busy all the time, was slower than running them one after the other.)
-template <typename T, int LOG_G, bool NARROW, bool WEIGHTED>
+template <typename T, int LOG_G, bool NARROW, int MODE>
 __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
+    constexpr bool VALS = MODE != kPlain;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // The launch has one workgroup more than the schedule needs; it writes the all-zero row of the Z
+    // buffer this layer fills and leaves.  (A workgroup of its own, so that no path of the others has
+    // a store before its reads of the schedule: those then stay scalar loads.)
+    if (blockIdx.x == gridDim.x - 1) {
+        if (a.out_z) {
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            for (int ch = threadIdx.x; ch < a.F / T::kVec; ch += 64 * kWaves)
+                *reinterpret_cast<uint4*>(a.out_z + (int64_t)a.n * a.F + ch * T::kVec) = zero;
+        }
+        return;
+    }
     const SchedHeader* h = a.sched.header;
+    const bool refuse = refused<T>(a);
     const int x = blockIdx.x % kXcds;
     const int64_t j = blockIdx.x / kXcds;   // position in this XCD's sequence
     const int64_t a_lo = h->xcd_first[x], a_hi = h->xcd_first[x + 1];
@@ -420,7 +484,7 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
     if (j < n_a) {
 #pragma unroll 1
         for (int64_t t = a_lo + j * kWaves + wave; t < a_hi; t += n_a * kWaves)
-            run_segment<T, LOG_G, NARROW, WEIGHTED>(a, a.sched.segs[t], lane);
+            run_segment<T, LOG_G, NARROW, MODE>(a, a.sched.segs[t], lane, refuse);
         return;
     }
     const int64_t o = j - n_a;                           // position among the B- and C-workgroups
@@ -431,7 +495,7 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
         const int64_t first = lo + ((o * kXcds + x) * kWaves + wave) * per_wave;
         const int64_t last = first + per_wave < hi ? first + per_wave : hi;
 #pragma unroll 1
-        for (int64_t t = first; t < last; ++t) run_segment<T, LOG_G, NARROW, WEIGHTED>(a, a.sched.segs[t], lane);
+        for (int64_t t = first; t < last; ++t) run_segment<T, LOG_G, NARROW, MODE>(a, a.sched.segs[t], lane, refuse);
         return;
     }
     const int64_t rb = (o - n_b) * kXcds + x;
@@ -446,26 +510,27 @@ __global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
         my_beg = a.sched.zrow_ptr[my_row];
         my_len = a.sched.zrow_ptr[my_row + 1] - my_beg;
         my_node = a.sched.orig[my_row];
-        my_s = a.dinv_sqrt[my_node];
+        my_s = row_scale<T>(a, my_node, refuse);
     }
     const int c = lane & (G - 1);
     const int g = lane >> LOG_G;
+    const int32_t none = MODE == kFirst ? 0 : a.n;
     int32_t beg = __shfl(my_beg, g), len = __shfl(my_len, g);
-    int32_t idx_cur = c < len ? __builtin_nontemporal_load(a.sched.zcol + beg + c) : a.n;
+    int32_t idx_cur = c < len ? *(a.cols + beg + c) : none;
     float wgt_cur = 0.0f;
-    if constexpr (WEIGHTED)
-        if (c < len) wgt_cur = __builtin_nontemporal_load(a.sched.zval + beg + c);
+    if constexpr (VALS)
+        if (c < len) wgt_cur = *(a.vals + beg + c);
 #pragma unroll 1
     for (int r0 = 0; r0 < n_rows; r0 += NB) {
         const int src = r0 + g;      // the row of this lane's group (lanes >= n_rows hold len -1)
         const int nxt = (src + NB) & 63;
         const int32_t nbeg = __shfl(my_beg, nxt);
         const int32_t nlen = r0 + NB < n_rows ? __shfl(my_len, nxt) : -1;
-        const int32_t idx_nxt = c < nlen ? __builtin_nontemporal_load(a.sched.zcol + nbeg + c) : a.n;
+        const int32_t idx_nxt = c < nlen ? *(a.cols + nbeg + c) : none;
         float wgt_nxt = 0.0f;
-        if constexpr (WEIGHTED)
-            if (c < nlen) wgt_nxt = __builtin_nontemporal_load(a.sched.zval + nbeg + c);
-        run_short_rows<T, LOG_G, NARROW, WEIGHTED>(a, beg, len, __shfl(my_row, src), __shfl(my_node, src),
+        if constexpr (VALS)
+            if (c < nlen) wgt_nxt = *(a.vals + nbeg + c);
+        run_short_rows<T, LOG_G, NARROW, MODE>(a, beg, len, __shfl(my_row, src), __shfl(my_node, src),
                                                    __shfl(my_s, src), idx_cur, wgt_cur, lane);
         beg = nbeg;
         len = nlen;
@@ -486,12 +551,13 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
     constexpr int kThreads = kReduceThreads;
     __shared__ double red[kThreads][4];
     const int32_t n_multi = a.sched.header->n_multi;
+    const bool refuse = refused<T>(a);
     for (int32_t m = blockIdx.x; m < n_multi; m += gridDim.x) {
     const int32_t k = a.sched.multi_row[m];  // internal row
     const int32_t node = a.sched.orig[k];
     const int32_t base = a.sched.slot_base[m];
     const int32_t cnt = a.sched.slot_cnt[m];
-    const float s = a.dinv_sqrt[node];
+    const float s = row_scale<T>(a, node, refuse);
     const int quads = a.F / 4;
     for (int q0 = 0; q0 < quads; q0 += kThreads) {
         const int width = quads - q0 < kThreads ? quads - q0 : kThreads;
@@ -532,15 +598,12 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_split_rows(const LayerA
 
 constexpr int kPrescaleThreads = 256;
 
+constexpr int64_t kDirectMaxNnz = 1 << 20;   // see run_layers
 constexpr int kPrescaleRows = 4;   // rows per thread: their dependent loads (row -> node -> x, s) overlap
 
-// Z(0) = S X(0) in internal row order: one streaming pass, 16 bytes of kPrescaleRows rows per
-// thread.  Also clears the zero rows (index n) of both Z buffers.
-// `transposed_of` is the schedule's header when the pass computes with the TRANSPOSE of the stored
-// operator (the backward entry points), else null.  Those entry points apply the stored operator
-// itself, which is its transpose only if structure and values are symmetric; a schedule that
-// e2eg_normalize found not to be is refused here, on the device, without a read-back: every row of
-// Z(0) becomes NaN, and so does the whole result.
+// Z = S_in X in internal row order: one streaming pass, 16 bytes of kPrescaleRows rows per thread.
+// Also clears the zero row (index n) of the Z buffer (of both, if z_other is given).  Used for Z(0) of a
+// multi-layer propagation (see run_layers) and by e2eg_aggregate, whose input scales depend on the mode.
 template <typename T>
 __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename T::elem* __restrict__ x,
                                                                    int64_t ldx,
@@ -548,8 +611,7 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
                                                                    const int32_t* __restrict__ orig,
                                                                    typename T::elem* __restrict__ z,
                                                                    typename T::elem* __restrict__ z_other,
-                                                                   int64_t n, int32_t F,
-                                                                   const SchedHeader* __restrict__ transposed_of) {
+                                                                   int64_t n, int32_t F) {
     constexpr int V = T::kVec;
     const int chunks = F / V;
     const int64_t id = (int64_t)blockIdx.x * kPrescaleThreads + threadIdx.x;
@@ -575,44 +637,42 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
             s[i] = dinv_sqrt[node[i]];
         }
     }
-    const bool refuse = transposed_of != nullptr && transposed_of->flags != 0;
 #pragma unroll
     for (int i = 0; i < kPrescaleRows; ++i) {
         const int64_t zrow = group * kPrescaleRows + i;
         if (zrow > n) continue;
 #pragma unroll
         for (int k = 0; k < V; ++k) v[i][k] *= s[i];   // the zero row: 0 * 0
-        if (refuse && zrow < n) {
-#pragma unroll
-            for (int k = 0; k < V; ++k) v[i][k] = __builtin_nanf("");
-        }
         store_vec<T>(z + zrow * F + col, v[i]);
         if (zrow == n && z_other) store_vec<T>(z_other + zrow * F + col, v[i]);
     }
 }
 
-template <typename T, bool NARROW, bool WEIGHTED>
+template <typename T, bool NARROW, int MODE>
 void launch_spmm(int log_g, dim3 grid, const LayerArgs<T>& a, hipStream_t stream) {
     const dim3 blk(64 * kWaves);
     switch (log_g) {
-        case 0: spmm_rows<T, 0, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        case 1: spmm_rows<T, 1, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        case 2: spmm_rows<T, 2, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        case 3: spmm_rows<T, 3, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        case 4: spmm_rows<T, 4, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        case 5: spmm_rows<T, 5, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
-        default: spmm_rows<T, 6, NARROW, WEIGHTED><<<grid, blk, 0, stream>>>(a); break;
+        case 0: spmm_rows<T, 0, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        case 1: spmm_rows<T, 1, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        case 2: spmm_rows<T, 2, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        case 3: spmm_rows<T, 3, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        case 4: spmm_rows<T, 4, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        case 5: spmm_rows<T, 5, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
+        default: spmm_rows<T, 6, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
     }
 }
 
+// `mode`: kPlain / kValues for a layer that reads a Z buffer (a.cols = zcol, a.vals = null / zval),
+// kFirst for one that reads the caller's rows (a.cols = znode, a.vals = zs, a.ld_in = their leading dimension).
 template <typename T>
-int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream) {
+int32_t launch_layer(LayerArgs<T>& a, int mode, int64_t n, int64_t nnz, hipStream_t stream) {
     const int chunks = a.F / T::kVec;
     int log_g = 0;
     while ((1 << log_g) < chunks && log_g < 6) ++log_g;
-    const uint64_t row_bytes = (uint64_t)a.F * sizeof(typename T::elem);
+    const uint64_t row_bytes = (uint64_t)a.ld_in * sizeof(typename T::elem);
     const uint64_t table_bytes = (uint64_t)(n + 1) * row_bytes;
-    const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24);
+    // 32-bit byte offsets formed by a 24-bit multiply: both factors below 2^24, the table below 4 GiB
+    const bool narrow = table_bytes <= 0xffffffffull && n + 1 <= (1 << 24) && row_bytes < (1u << 24);
     // upper bounds of the three kinds of workgroup (see spmm_rows), per XCD, times the XCDs.  The bound
     // on slotted segments is about three times what a graph really has, so an eighth of it per XCD
     // covers every stretch the deal by entry counts produces in practice; a longer one goes round again.
@@ -623,13 +683,18 @@ int32_t launch_layer(LayerArgs<T>& a, int64_t n, int64_t nnz, hipStream_t stream
     a.n = (int32_t)n;
     a.a_blocks = (int32_t)a_blocks;
     a.b_blocks = (int32_t)b_blocks;
-    const dim3 grid((unsigned)(kXcds * (a_blocks + b_blocks + c_blocks)));
+    const dim3 grid((unsigned)(kXcds * (a_blocks + b_blocks + c_blocks) + 1));   // the last one: see spmm_rows
     profile_mark(stream, false);
-    const bool weighted = a.sched.zval != nullptr;
-    if (narrow && weighted) launch_spmm<T, true, true>(log_g, grid, a, stream);
-    else if (narrow) launch_spmm<T, true, false>(log_g, grid, a, stream);
-    else if (weighted) launch_spmm<T, false, true>(log_g, grid, a, stream);
-    else launch_spmm<T, false, false>(log_g, grid, a, stream);
+    if (mode == kFirst) {
+        if (narrow) launch_spmm<T, true, kFirst>(log_g, grid, a, stream);
+        else launch_spmm<T, false, kFirst>(log_g, grid, a, stream);
+    } else if (mode == kValues) {
+        if (narrow) launch_spmm<T, true, kValues>(log_g, grid, a, stream);
+        else launch_spmm<T, false, kValues>(log_g, grid, a, stream);
+    } else {
+        if (narrow) launch_spmm<T, true, kPlain>(log_g, grid, a, stream);
+        else launch_spmm<T, false, kPlain>(log_g, grid, a, stream);
+    }
     profile_mark(stream, true);
     E2EG_LAUNCH_CHECK("spmm_rows");
     if (nnz > kSegLen) {  // otherwise no row has several segments
@@ -695,30 +760,55 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     using E = typename T::elem;
     SchedView view;
     sched_carve(const_cast<void*>(sched), n, nnz, &view, weighted);
-    const int chunks = F / T::kVec;
-    E* z_cur = static_cast<E*>(w.z[0]);
-    E* z_next = static_cast<E*>(w.z[1]);
-    prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
-                       dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig, z_cur,
-                                                            z_next, n, F, transposed ? view.header : nullptr);
-    E2EG_LAUNCH_CHECK("prescale_rows");
+    // Layer l > 1 reads Z(l-1), which layer l-1 wrote into one of the two Z buffers (each launch also
+    // writes the all-zero row of the buffer it fills).  Layer 1 reads either Z(0), made by a streaming
+    // pre-scale pass, or the caller's rows themselves (kFirst).  The direct form saves that pass and
+    // its launch but is the slower kernel (a value per entry to read, hand round and multiply by; fewer
+    // resident wavefronts at some widths): measured, it pays where the pass cannot be spread over
+    // several layers or costs as much as the layers do - a single-layer call (every layer of a
+    // mini-batch step, between two dense updates, is one) and graphs of at most kDirectMaxNnz entries
+    // - and loses 2 % (50 M edges, K = 3) to 12 % (500 M edges, 128-byte rows) elsewhere.
+    const bool direct = K == 1 || nnz <= kDirectMaxNnz;
+    E* z_bufs[2] = {static_cast<E*>(w.z[0]), static_cast<E*>(w.z[1])};
+    int cur = -1;   // the Z buffer the next layer reads; -1: the caller's rows
+    if (!direct) {
+        const int chunks = F / T::kVec;
+        prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
+                           dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig,
+                                                                z_bufs[0], nullptr, n, F);
+        E2EG_LAUNCH_CHECK("prescale_rows");
+        cur = 0;
+    }
     for (int32_t l = 1; l <= K; ++l) {
         LayerArgs<T> a;
         a.dinv_sqrt = dinv;
         a.sched = view;
-        a.zin = z_cur;
+        a.transposed = transposed ? 1 : 0;
+        int mode;
+        if (cur < 0) {
+            a.zin = static_cast<const E*>(in);
+            a.ld_in = ld_in;
+            a.cols = view.znode;
+            a.vals = view.zs;
+            mode = kFirst;
+        } else {
+            a.zin = z_bufs[cur];
+            a.ld_in = F;
+            a.cols = view.zcol;
+            a.vals = weighted ? view.zval : nullptr;
+            mode = weighted ? kValues : kPlain;
+        }
+        const int nxt = cur < 0 ? 0 : 1 - cur;
         a.out_h = store[l - 1];
         a.ld_h = ld_store[l - 1];
-        a.out_z = l < K ? z_next : nullptr;
+        a.out_z = l < K ? z_bufs[nxt] : nullptr;
         a.addend = add ? add[l - 1] : nullptr;
         a.ld_add = ld_add;
         a.partial = w.partial;
         a.F = F;
-        int32_t st = launch_layer<T>(a, n, nnz, stream);
+        int32_t st = launch_layer<T>(a, mode, n, nnz, stream);
         if (st != E2EG_OK) return st;
-        E* t = z_cur;
-        z_cur = z_next;
-        z_next = t;
+        cur = nxt;
     }
     return E2EG_OK;
 }
@@ -772,13 +862,16 @@ int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_p
     const int chunks = F / T::kVec;
     prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(x), ldx, w.scale_in, view.orig,
-                                                            static_cast<E*>(w.z), nullptr, n, F,
-                                                            mode == E2EG_AGG_MEAN_T ? view.header : nullptr);
+                                                            static_cast<E*>(w.z), nullptr, n, F);
     E2EG_LAUNCH_CHECK("prescale_rows");
     LayerArgs<T> a;
     a.dinv_sqrt = w.scale_out;
     a.sched = view;
     a.zin = static_cast<const E*>(w.z);
+    a.ld_in = F;
+    a.cols = view.zcol;
+    a.vals = nullptr;
+    a.transposed = mode == E2EG_AGG_MEAN_T ? 1 : 0;
     a.out_h = static_cast<E*>(y);
     a.ld_h = ldy;
     a.out_z = nullptr;
@@ -786,7 +879,7 @@ int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_p
     a.ld_add = ld_add;
     a.partial = w.partial;
     a.F = F;
-    return launch_layer<T>(a, n, nnz, stream);
+    return launch_layer<T>(a, kPlain, n, nnz, stream);
 }
 
 constexpr int kMaxLayers = 64;

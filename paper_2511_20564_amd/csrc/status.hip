@@ -66,6 +66,8 @@ size_t sched_carve(void* base, int64_t n, int64_t nnz, SchedView* view, bool wei
     v.slot_base = c.take<int32_t>(v.max_multi);
     v.slot_cnt = c.take<int32_t>(v.max_multi);
     v.segs = c.take<Segment>(v.max_seg);
+    v.znode = c.take<int32_t>(nnz > 0 ? nnz : 1);
+    v.zs = c.take<float>(nnz > 0 ? nnz : 1);
     v.zval = weighted ? c.take<float>(nnz > 0 ? nnz : 1) : nullptr;  // last: the rest of the layout is shared
     if (view) *view = v;
     return c.size();

@@ -4,12 +4,18 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import progress
 from parity import assert_close, errors, to_device, to_f64
 from workloads import make_config, make_features
 
 pytestmark = pytest.mark.gpu
 
-DW_TOL = 1e-3   # dW is stored in fp32; its error is fp32 accumulation over the n node rows
+# dW is stored in fp32.  A product of two bf16 values is exact in fp32; a workgroup adds the products of
+# its node rows (at most max(128, n/256 rounded up to 64) of them, under 800 for n <= 200 k) in fp32, which
+# can lose at most 800 * 2^-24 = 4.8e-5 of the abs-sum; the workgroups' partial sums are added in double.
+# The bound asserted is twice that, on the componentwise error against the abs-sum  |P|^T |dZ|  (the
+# norm-wise ratio has no such bound: a sum of products with random signs is far smaller than its abs-sum).
+DW_TOL = 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -52,7 +58,7 @@ def test_transform_fwd_bwd(dev, oracle, n, Fin, Fout, relu):
     dZabs = np.abs(oracle.as_f64(gHb)) * ((oracle.as_f64(bits(H)) > 0) if relu else 1.0)
     assert_close(to_f64(gP), dPr, dZabs @ np.abs(oracle.as_f64(Wb)).T, "bf16", "transform dP")
     comp, norm = errors(to_f64(gW), dWr, np.abs(oracle.as_f64(Pb)).T @ dZabs)
-    assert comp <= DW_TOL and norm <= DW_TOL, (comp, norm)
+    assert comp <= DW_TOL, (comp, norm)
 
 
 def test_minibatch_pipeline(dev, oracle):
@@ -109,7 +115,8 @@ def run_minibatch(dev, oracle, c):
         dZabs = np.abs(oracle.as_f64(bits(gH))) * ((oracle.as_f64(bits(H[l + 1])) > 0) if relu else 1.0)
         assert_close(to_f64(gP), dPr, dZabs @ absW[l].T, "bf16", f"dP{l + 1}")
         comp, norm = errors(to_f64(gW), dWr, np.abs(oracle.as_f64(bits(P[l]))).T @ dZabs)
-        assert comp <= DW_TOL and norm <= DW_TOL, (l, comp, norm)
+        assert comp <= DW_TOL, (l, comp, norm)
+        progress(f"mini-batch layer {l + 1}: dW componentwise {comp:.2e} normwise {norm:.2e} (tol {DW_TOL})")
         ref = oracle.propagate_layer_transposed(row_ptr, col, oracle.as_f64(bits(gP)))
         sc = oracle.propagate_layer_transposed(row_ptr, col, np.abs(oracle.as_f64(bits(gP))))
         assert_close(to_f64(gHprev), ref, sc, "bf16", f"gH{l}")
