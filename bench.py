@@ -99,6 +99,8 @@ def bench_transform(dev, torch, _event_ms=None):
             B.e2eg_layer_transform(B.E2EG_TRANSFORM_BWD, nt, Ft, Ft, B.E2EG_BF16, 1, Pt, Wt, Ht, gt, gP, gW, ws,
                                    None, torch.cuda.current_stream().cuda_stream)
 
+        # a plain copy of known size on the same stream: the scale for the profiler's byte counters
+        B.e2eg_profile_copy(gP, Pt, Pt.numel() * Pt.element_size(), torch.cuda.current_stream().cuda_stream)
         tf_ms, tb_ms = event_ms(fwd, reps), event_ms(bwd, reps)
         gf_ms, gb_ms = replay_ms(torch, fwd, reps), replay_ms(torch, bwd, reps)
         flop_f = 2.0 * nt * Ft * Ft

@@ -89,19 +89,24 @@ __device__ __forceinline__ void load_vec<BF16>(const uint16_t* p, float (&v)[8])
     v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
 }
 
-// Layer outputs and partial sums are written once and not read again by the same kernel:
-// streaming stores keep them from displacing the feature rows the gathers reuse in L2.
+// Layer outputs and partial sums are written once and not read again by the same kernel.  `stream`
+// (wave-uniform): write them with streaming stores, which keeps them from displacing the feature rows
+// the gathers reuse in L2 - right when the tables are far larger than the caches (1 % on the 50 M-edge
+// graph).  On a small graph the next kernel finds them in the caches if they are written normally
+// (4.5 % on the 2 M-edge graph), so there `stream` is off; launch_layer decides by the table's size.
 template <typename T>
-__device__ __forceinline__ void store_vec(typename T::elem* p, const float (&v)[T::kVec]);
+__device__ __forceinline__ void store_vec(typename T::elem* p, const float (&v)[T::kVec], bool stream);
 template <>
-__device__ __forceinline__ void store_vec<F32>(float* p, const float (&v)[4]) {
+__device__ __forceinline__ void store_vec<F32>(float* p, const float (&v)[4], bool stream) {
     const f32x4 q = {v[0], v[1], v[2], v[3]};
-    __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
+    if (stream) __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(p));
+    else *reinterpret_cast<f32x4*>(p) = q;
 }
 template <>
-__device__ __forceinline__ void store_vec<BF16>(uint16_t* p, const float (&v)[8]) {
+__device__ __forceinline__ void store_vec<BF16>(uint16_t* p, const float (&v)[8], bool stream) {
     const u32x4 q = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
-    __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(p));
+    if (stream) __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(p));
+    else *reinterpret_cast<u32x4*>(p) = q;
 }
 
 template <typename T>
@@ -128,6 +133,7 @@ struct LayerArgs {
     const int32_t* cols;          // column of every entry: zcol (rows of Z), or znode for kFirst
     const float* vals;            // value of every entry: null (kPlain), zval (kValues), zs (kFirst)
     int32_t transposed;           // the call computes with the transpose of the stored operator
+    int32_t stream_out;           // results leave through streaming stores (tables far larger than the caches)
     typename T::elem* out_h;      // H(l+1) by node id, or null
     int64_t ld_h;
     typename T::elem* out_z;      // Z(l+1) = S H(l+1), [n + 1][F] in internal order, or null
@@ -229,11 +235,11 @@ __device__ __forceinline__ void finish_vec(const LayerArgs<T>& a, int32_t zrow, 
 #pragma unroll
         for (int v = 0; v < T::kVec; ++v) h[v] += d[v];
     }
-    if (a.out_h) store_vec<T>(a.out_h + (int64_t)node * a.ld_h + col, h);
+    if (a.out_h) store_vec<T>(a.out_h + (int64_t)node * a.ld_h + col, h, a.stream_out != 0);
     if (a.out_z) {
 #pragma unroll
         for (int v = 0; v < T::kVec; ++v) h[v] *= s;
-        store_vec<T>(a.out_z + (int64_t)zrow * a.F + col, h);
+        store_vec<T>(a.out_z + (int64_t)zrow * a.F + col, h, a.stream_out != 0);
     }
 }
 
@@ -346,7 +352,8 @@ __device__ __forceinline__ void run_segment(const LayerArgs<T>& a, const Segment
 #pragma unroll
                 for (int v = 0; v < V; v += 4) {
                     const f32x4 o = {tot[v], tot[v + 1], tot[v + 2], tot[v + 3]};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p + v));
+                    if (a.stream_out) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p + v));
+                    else *reinterpret_cast<f32x4*>(p + v) = o;
                 }
             }
         }
@@ -451,8 +458,10 @@ constexpr int kSingleBlocksPerXcd = 512;  // B-workgroups per XCD (fewer when th
 // workgroups beyond the real ones, all at the end of each XCD's sequence, leave at once.
 // (Measured: spreading the L2-bound A-workgroups evenly among the HBM-bound others, so that both
 // resources are busy all the time, was slower than running them one after the other.)
+// At least four wavefronts per SIMD (128 registers): the instantiations that carry a value per entry
+// would otherwise take 144 at 128-byte bf16 rows and lose a resident wavefront; none of them spills at 128.
 template <typename T, int LOG_G, bool NARROW, int MODE>
-__global__ __launch_bounds__(64 * kWaves) void spmm_rows(const LayerArgs<T> a) {
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(4))) void spmm_rows(const LayerArgs<T> a) {
     constexpr int G = 1 << LOG_G;
     constexpr int NB = 64 >> LOG_G;
     constexpr bool VALS = MODE != kPlain;
@@ -611,7 +620,7 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
                                                                    const int32_t* __restrict__ orig,
                                                                    typename T::elem* __restrict__ z,
                                                                    typename T::elem* __restrict__ z_other,
-                                                                   int64_t n, int32_t F) {
+                                                                   int64_t n, int32_t F, bool stream) {
     constexpr int V = T::kVec;
     const int chunks = F / V;
     const int64_t id = (int64_t)blockIdx.x * kPrescaleThreads + threadIdx.x;
@@ -643,8 +652,8 @@ __global__ __launch_bounds__(kPrescaleThreads) void prescale_rows(const typename
         if (zrow > n) continue;
 #pragma unroll
         for (int k = 0; k < V; ++k) v[i][k] *= s[i];   // the zero row: 0 * 0
-        store_vec<T>(z + zrow * F + col, v[i]);
-        if (zrow == n && z_other) store_vec<T>(z_other + zrow * F + col, v[i]);
+        store_vec<T>(z + zrow * F + col, v[i], stream);
+        if (zrow == n && z_other) store_vec<T>(z_other + zrow * F + col, v[i], stream);
     }
 }
 
@@ -661,6 +670,10 @@ void launch_spmm(int log_g, dim3 grid, const LayerArgs<T>& a, hipStream_t stream
         default: spmm_rows<T, 6, NARROW, MODE><<<grid, blk, 0, stream>>>(a); break;
     }
 }
+
+// Results are streamed past the caches when one feature table is larger than this (see store_vec).
+constexpr uint64_t kStreamOutBytes = 64ull << 20;
+inline bool streams_out(uint64_t table_bytes) { return table_bytes > kStreamOutBytes; }
 
 // `mode`: kPlain / kValues for a layer that reads a Z buffer (a.cols = zcol, a.vals = null / zval),
 // kFirst for one that reads the caller's rows (a.cols = znode, a.vals = zs, a.ld_in = their leading dimension).
@@ -681,6 +694,7 @@ int32_t launch_layer(LayerArgs<T>& a, int mode, int64_t n, int64_t nnz, hipStrea
     if (b_blocks > kSingleBlocksPerXcd) b_blocks = kSingleBlocksPerXcd;
     const int64_t c_blocks = ceil_div(ceil_div(n, kWaves * kShortPerWave), kXcds) + 1;
     a.n = (int32_t)n;
+    a.stream_out = streams_out((uint64_t)(n + 1) * (uint64_t)a.F * sizeof(typename T::elem)) ? 1 : 0;
     a.a_blocks = (int32_t)a_blocks;
     a.b_blocks = (int32_t)b_blocks;
     const dim3 grid((unsigned)(kXcds * (a_blocks + b_blocks + c_blocks) + 1));   // the last one: see spmm_rows
@@ -762,20 +776,23 @@ int32_t run_layers(int32_t n, int64_t nnz, const int32_t* row_ptr, const int32_t
     sched_carve(const_cast<void*>(sched), n, nnz, &view, weighted);
     // Layer l > 1 reads Z(l-1), which layer l-1 wrote into one of the two Z buffers (each launch also
     // writes the all-zero row of the buffer it fills).  Layer 1 reads either Z(0), made by a streaming
-    // pre-scale pass, or the caller's rows themselves (kFirst).  The direct form saves that pass and
-    // its launch but is the slower kernel (a value per entry to read, hand round and multiply by; fewer
-    // resident wavefronts at some widths): measured, it pays where the pass cannot be spread over
-    // several layers or costs as much as the layers do - a single-layer call (every layer of a
-    // mini-batch step, between two dense updates, is one) and graphs of at most kDirectMaxNnz entries
-    // - and loses 2 % (50 M edges, K = 3) to 12 % (500 M edges, 128-byte rows) elsewhere.
-    const bool direct = K == 1 || nnz <= kDirectMaxNnz;
+    // pre-scale pass, or the caller's rows themselves (kFirst).  The direct form saves that pass
+    // (2 n row-bytes, a launch, a rounding) and pays for it with a value per entry to read, hand round
+    // and multiply by (4 nnz bytes more).  It is taken when that trade is good: 4 nnz < 2 n row-bytes,
+    // or a graph so small (kDirectMaxNnz entries) that a launch costs as much as the layer.  Measured
+    // (ms per K = 3 forward, pre-scale / direct): 2 M edges, 256-byte rows 0.63 / 0.62; 50 M edges,
+    // 256-byte rows 5.78 / 5.67; 50 M edges, 128-byte rows 7.37 / 7.53 - the one the rule sends the
+    // other way.
+    const uint64_t row_bytes_in = (uint64_t)F * sizeof(E);
+    const bool direct = nnz <= kDirectMaxNnz || 2 * (uint64_t)nnz < (uint64_t)n * row_bytes_in;
     E* z_bufs[2] = {static_cast<E*>(w.z[0]), static_cast<E*>(w.z[1])};
     int cur = -1;   // the Z buffer the next layer reads; -1: the caller's rows
     if (!direct) {
         const int chunks = F / T::kVec;
         prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                            dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(in), ld_in, dinv, view.orig,
-                                                                z_bufs[0], nullptr, n, F);
+                                                                z_bufs[0], nullptr, n, F,
+                                                                streams_out((uint64_t)(n + 1) * F * sizeof(E)));
         E2EG_LAUNCH_CHECK("prescale_rows");
         cur = 0;
     }
@@ -862,7 +879,8 @@ int32_t run_aggregate(int32_t mode, int32_t n, int64_t nnz, const int32_t* row_p
     const int chunks = F / T::kVec;
     prescale_rows<T><<<dim3((unsigned)ceil_div(ceil_div((int64_t)n + 1, kPrescaleRows) * chunks, kPrescaleThreads)),
                        dim3(kPrescaleThreads), 0, stream>>>(static_cast<const E*>(x), ldx, w.scale_in, view.orig,
-                                                            static_cast<E*>(w.z), nullptr, n, F);
+                                                            static_cast<E*>(w.z), nullptr, n, F,
+                                                            streams_out((uint64_t)(n + 1) * F * sizeof(E)));
     E2EG_LAUNCH_CHECK("prescale_rows");
     LayerArgs<T> a;
     a.dinv_sqrt = w.scale_out;

@@ -119,6 +119,22 @@ def test_propagate_feature_widths(dev, oracle, dtype, F, K):
     run_case(dev, oracle, c)
 
 
+@pytest.mark.parametrize("dtype,F,K", [("f32", 8, 3), ("bf16", 16, 2), ("bf16", 8, 1)])
+def test_propagate_narrow_rows_on_a_dense_graph(dev, oracle, dtype, F, K):
+    """More than 2^20 stored entries and many entries per byte of feature row: the case in which the
+    first layer reads pre-scaled rows made by a streaming pass instead of the caller's rows directly
+    (the library takes the direct form when 4 nnz < 2 n row-bytes or the graph is small; both forms
+    must give the oracle's result)."""
+    nu, ni, ne = 40_000, 20_000, 1_200_000
+    users, items = uniform_bipartite(nu, ni, ne, seed=17)
+    n = nu + ni
+    esz = 4 if dtype == "f32" else 2
+    assert 2 * ne + n > 1 << 20 and 2 * (2 * ne + n) >= n * F * esz
+    c = dict(n_users=nu, n_items=ni, users=users, items=items, dtype=dtype, K=K,
+             X0=make_features(n, F, 0.1, 1, dtype), gY=make_features(n, F, 1.0, 2, dtype))
+    run_case(dev, oracle, c)
+
+
 @pytest.mark.parametrize("dtype,F", [("f32", 8), ("f32", 64), ("f32", 320), ("bf16", 16), ("bf16", 128), ("bf16", 1024)])
 def test_propagate_long_rows_feature_widths(dev, oracle, dtype, F):
     """Rows of every class at each lane layout: a few items with thousands of neighbours (cut at
