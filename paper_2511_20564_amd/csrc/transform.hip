@@ -19,15 +19,25 @@
 namespace e2eg {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kRowsPerBlock = 32 * kWaves;   // one 32-row MFMA tile per wavefront
+constexpr int kDenseWaves = 8;               // wavefronts per workgroup of dense_rows (4 where a row has more than 8 k-steps
+                                             // and a wavefront needs more than 256 registers): they share one weight tile
+constexpr int kDenseDepth = 1;               // tiles a wavefront of dense_rows requests ahead (2 measured slower: 25.4 against
+                                             // 23.3 us at 200 k rows, 408 against 392 us at 4 M)
+constexpr int kGradWaves = 8;                // wavefronts per workgroup of weight_grad_partial
+constexpr int kGradThreads = 64 * kGradWaves;
+constexpr int kReduceThreads = 256;
 constexpr int kMaxF = 256;
+constexpr int kDenseMaxGroups = 256;         // workgroups of 8 wavefronts of dense_rows per column group: their registers
+                                             // allow one per compute unit
 constexpr int kPad = 8;                      // LDS row padding (elements) against bank conflicts
 constexpr int kWeightLds = 128 * (128 + kPad);  // elements; also fits 64 x (256 + kPad)
 constexpr int kOutLd = 128 + kPad;           // pitch of a wavefront's result rows in LDS (at most 128 columns per workgroup)
-constexpr int kTileRows = 64;                // node rows per step of the dW kernel
-constexpr int kRowPasses = kTileRows / 32;   // a thread stages one row of every 32
+constexpr int kTileRows = 128;               // node rows per step of the dW kernel
+constexpr int kPairPasses = kTileRows / 64;  // a thread stages one pair of rows of every 32 pairs ...
+constexpr int kChunkLanes = kGradThreads / 32;        // ... and one 8-column chunk of every kChunkLanes
+constexpr int kChunkReps = 16 / kChunkLanes;          // (a 128-column tile has 16 chunks)
+constexpr int kGradOSplit = kGradWaves / 4;  // wavefronts that share a 32-column block of P split the dZ columns
+constexpr int kGradOBlocks = 4 / kGradOSplit;
 constexpr int kTileLd = kTileRows + 8;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -61,23 +71,31 @@ __device__ __forceinline__ uint4 mask_vec(uint4 g, uint4 h) {
 
 // out[r][c] = act( sum_k A[r][k] * B(c, k) ),  A = rows of `a_rows` (masked by `mask_rows` > 0
 // when MASKED), B(c, k) = TRANS_W ? w[k][c] : w[c][k].
-// grid.x: blocks of `tiles` x 128 rows (the weight tile is staged once per workgroup and serves
-// all its row tiles); grid.y: groups of `ngroup` output columns.
+// grid.x: workgroups that each take `tiles` blocks of 32 WAVES rows, block b + t * gridDim.x in
+// turn t, so that at any moment the workgroups in flight read and write one moving stretch of the
+// tables (the weight tile is staged once per workgroup and serves all its turns); grid.y: groups of
+// `ngroup` output columns.
 // KS: the most k-steps of 16 a row can have (8 for up to 128 input columns).  A wavefront requests
-// the rows of its next tile before it multiplies the current one, so that the loads overlap the
-// product and the stores.
+// the rows of its next kDenseDepth tiles before it multiplies the current one, so that the loads
+// overlap the staging of the weights, the product and the stores.
 // EXACT: kdim == 16 * KS and every workgroup has 128 output columns, so that the loops over
 // k-steps and column blocks have constant bounds and compile to straight-line code.
-template <bool MASKED, bool TRANS_W, bool RELU, int KS, bool EXACT>
-__global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restrict__ a_rows,
+template <bool MASKED, bool TRANS_W, bool RELU, int KS, bool EXACT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restrict__ a_rows,
                                                        const uint16_t* __restrict__ mask_rows,
                                                        const uint16_t* __restrict__ w,
                                                        uint16_t* __restrict__ out, int32_t n,
                                                        int32_t kdim, int32_t ndim, int32_t w_ld,
                                                        int32_t ngroup, int32_t tiles, int32_t stream_out) {
-    __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][kdim + kPad]
-    __shared__ __attribute__((aligned(16))) uint16_t ot[kWaves][16 * kOutLd];  // per wavefront: 16 result rows
-    const int ldb = kdim + kPad;
+    __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][ldb]
+    __shared__ __attribute__((aligned(16))) uint16_t ot[WAVES][16 * kOutLd];  // per wavefront: 16 result rows
+    // Layout of the weight tile: k contiguous per output column c.  Copied as it is (W already k-contiguous)
+    // the rows are padded by kPad, which spreads a wavefront's 16-byte reads of 32 columns over the banks.
+    // Transposed on the way in, and kdim a multiple of 64, the rows are not padded; instead the 16-byte
+    // groups of row c are stored at group index ^ swizzle(c), swizzle(c) = (c + c / 8) % 8: the reads stay
+    // spread, and so do the transposing 4-byte writes (see below), which padding alone cannot achieve.
+    const bool swz = TRANS_W && (EXACT || kdim % 64 == 0);
+    const int ldb = swz ? kdim : kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
     const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
     const int lane = threadIdx.x & 63;
@@ -99,26 +117,42 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
             }
         }
     };
-    const int64_t row_first = (int64_t)blockIdx.x * tiles * kRowsPerBlock + wave * 32 + l32;
-    uint4 nxt_a[KS], nxt_m[MASKED ? KS : 1];
-    load_rows(row_first, nxt_a, nxt_m);   // in flight while the weight tile is staged
-    // stage the weight tile, k contiguous per output column.  Transposing: consecutive lanes take
-    // consecutive k, so that their 2-byte LDS writes fall into consecutive banks.
+    constexpr int kDenseThreads = 64 * WAVES;
+    constexpr int kRowsPerBlock = 32 * WAVES;   // one 32-row MFMA tile per wavefront
+    const int swz0 = l32 + (l32 >> 3);   // swizzle of column nb * 32 + l32 is (swz0 + 4 nb) % 8
+    const int64_t row_first = (int64_t)blockIdx.x * kRowsPerBlock + wave * 32 + l32;
+    const int64_t row_step = (int64_t)gridDim.x * kRowsPerBlock;
+    // tiles requested ahead of the one being multiplied (each holds KS, masked 2 KS, 16-byte registers)
+    constexpr int DEPTH = (MASKED || KS > 8) ? 1 : kDenseDepth;
+    uint4 nxt_a[DEPTH][KS], nxt_m[DEPTH][MASKED ? KS : 1];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load_rows(row_first + d * row_step, nxt_a[d], nxt_m[d]);   // in flight while the weight tile is staged
     if (TRANS_W) {
+        // A thread takes the same 8 columns of two consecutive rows of W (k = 2 kp, 2 kp + 1), 16 bytes
+        // each -- a wavefront reads whole 128-byte lines -- and writes, for each of the 8 columns, the pair
+        // as one 4-byte word into that column's row of the tile.  The 64 lanes of a store instruction hold
+        // 4 values of kp and 16 column chunks; the swizzle sends them to 32 different banks, two lanes each.
         const int cvecs = ng / 8;
-        for (int e = threadIdx.x; e < kdim * cvecs; e += kThreads) {
-            const int cv = e / kdim, k = e - cv * kdim;
-            const uint4 q = *reinterpret_cast<const uint4*>(w + (int64_t)k * w_ld + n0 + cv * 8);
-            const uint32_t words[4] = {q.x, q.y, q.z, q.w};
+        uint32_t* bt32 = reinterpret_cast<uint32_t*>(bt);
+        const int ldw = ldb / 2;
+        for (int e = threadIdx.x; e < (kdim / 2) * cvecs; e += kDenseThreads) {
+            const int kp = e / cvecs, ch = e - kp * cvecs;
+            const uint16_t* src = w + (int64_t)(2 * kp) * w_ld + n0 + ch * 8;
+            const uint4 q0 = *reinterpret_cast<const uint4*>(src);
+            const uint4 q1 = *reinterpret_cast<const uint4*>(src + w_ld);
+            const uint32_t w0[4] = {q0.x, q0.y, q0.z, q0.w};
+            const uint32_t w1[4] = {q1.x, q1.y, q1.z, q1.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                bt[(cv * 8 + 2 * j) * ldb + k] = (uint16_t)(words[j] & 0xffffu);
-                bt[(cv * 8 + 2 * j + 1) * ldb + k] = (uint16_t)(words[j] >> 16);
+                const int c = ch * 8 + 2 * j;
+                const int g0 = swz ? ((c + (c >> 3)) & 7) : 0, g1 = swz ? ((c + 1 + ((c + 1) >> 3)) & 7) : 0;
+                bt32[c * ldw + ((((kp >> 2) ^ g0) << 2) | (kp & 3))] = (w0[j] & 0xffffu) | (w1[j] << 16);
+                bt32[(c + 1) * ldw + ((((kp >> 2) ^ g1) << 2) | (kp & 3))] = (w0[j] >> 16) | (w1[j] & 0xffff0000u);
             }
         }
     } else {
         const int kvecs = kdim / 8;
-        for (int e = threadIdx.x; e < ng * kvecs; e += kThreads) {
+        for (int e = threadIdx.x; e < ng * kvecs; e += kDenseThreads) {
             const int c = e / kvecs, kv = e - c * kvecs;
             *reinterpret_cast<uint4*>(bt + c * ldb + kv * 8) =
                 *reinterpret_cast<const uint4*>(w + (int64_t)(n0 + c) * w_ld + kv * 8);
@@ -128,13 +162,21 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
 
 #pragma unroll 1
     for (int tile = 0; tile < tiles; ++tile) {
-    const int64_t row = row_first + (int64_t)tile * kRowsPerBlock;
+    const int64_t row = row_first + tile * row_step;
     if ((int64_t)row - l32 >= n) return;   // the whole wavefront is past the end
 
     uint4 areg[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) areg[ks] = MASKED ? mask_vec(nxt_a[ks], nxt_m[ks]) : nxt_a[ks];
-    if (tile + 1 < tiles) load_rows(row + kRowsPerBlock, nxt_a, nxt_m);
+    for (int ks = 0; ks < KS; ++ks) areg[ks] = MASKED ? mask_vec(nxt_a[0][ks], nxt_m[0][ks]) : nxt_a[0][ks];
+#pragma unroll
+    for (int d = 0; d + 1 < DEPTH; ++d) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            nxt_a[d][ks] = nxt_a[d + 1][ks];
+            if (MASKED) nxt_m[d][ks] = nxt_m[d + 1][ks];
+        }
+    }
+    if (tile + DEPTH < tiles) load_rows(row + DEPTH * row_step, nxt_a[DEPTH - 1], nxt_m[DEPTH - 1]);
     f32x16 acc[4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb)
@@ -146,7 +188,8 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
                 if (nb < nblocks) {
-                    const uint4 b = *reinterpret_cast<const uint4*>(bt + (nb * 32 + l32) * ldb + ks * 16 + khalf * 8);
+                    const int grp = (ks * 2 + khalf) ^ (swz ? ((swz0 + 4 * nb) & 7) : 0);
+                    const uint4 b = *reinterpret_cast<const uint4*>(bt + (nb * 32 + l32) * ldb + grp * 8);
                     acc[nb] = mfma(b, areg[ks], acc[nb]);  // D[out column][row]
                 }
             }
@@ -207,8 +250,12 @@ __global__ __launch_bounds__(kThreads) void dense_rows(const uint16_t* __restric
 
 // partial[blockIdx.x][c][o] = sum over this block's node rows of P[r][c] * dZ[r][o].
 // grid.y / grid.z: groups of 128 columns of P / of dZ.
+// The node rows are the contraction index, so both operands go through LDS transposed, kTileRows rows a
+// step.  A thread takes the same 8 columns of two consecutive rows and writes, for each column, the pair as
+// one 4-byte word: consecutive lanes hold consecutive row pairs, so a store instruction fills consecutive
+// banks.  The rows of the next two steps are requested while the current one is multiplied.
 template <bool MASKED>
-__global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* __restrict__ p,
+__global__ __launch_bounds__(kGradThreads) void weight_grad_partial(const uint16_t* __restrict__ p,
                                                                 const uint16_t* __restrict__ gh,
                                                                 const uint16_t* __restrict__ h,
                                                                 float* __restrict__ partial, int32_t n,
@@ -223,103 +270,126 @@ __global__ __launch_bounds__(kThreads) void weight_grad_partial(const uint16_t* 
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
     const int khalf = lane >> 5;
-    // staging: consecutive lanes take consecutive tile rows (their 2-byte writes into the
-    // transposed tiles then fall into consecutive banks); a thread stages two 8-column chunks
-    const int lr = threadIdx.x & 31;   // tile row
-    const int cq = threadIdx.x >> 5;   // 8-column chunk cq (and cq + 8)
+    const int rp = threadIdx.x & 31;   // row pair of the tile (and every 32nd after it)
+    const int cq = threadIdx.x >> 5;   // 8-column chunk (and every kChunkLanes-th after it)
     const int oblocks = og / 32;
-    const bool wave_live = wave * 32 < cg;
+    // products: this wavefront owns 32 columns of P and kGradOBlocks blocks of 32 columns of dZ
+    const int cw = wave & 3;
+    const int ob0 = (wave >> 2) * kGradOBlocks;
+    const bool wave_live = cw * 32 < cg && ob0 < oblocks;
 
-    f32x16 acc[4];
+    f32x16 acc[kGradOBlocks];
 #pragma unroll
-    for (int ob = 0; ob < 4; ++ob)
+    for (int ob = 0; ob < kGradOBlocks; ++ob)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[ob][i] = 0.0f;
 
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r_end = r_begin + rows_per_block < n ? r_begin + rows_per_block : n;
-    // this thread's pieces of one 32-row step: row r0 + lr, column chunks cq and cq + 8 of P and of dZ
-    // (dZ with its mask still beside it)
-    uint4 qp[2 * kRowPasses], qz[2 * kRowPasses], qh[MASKED ? 2 * kRowPasses : 1];
-    auto load_step = [&](int64_t r0) {
+    // A thread's pieces of one step: for each of its row pairs and column chunks, two rows of P and of dZ
+    // (dZ with its mask still beside it).  Piece i: chunk rep i % kChunkReps, pair pass i / kChunkReps.
+    constexpr int kPieces = kChunkReps * kPairPasses;
+    struct Step {
+        uint4 p0[kPieces], p1[kPieces], z0[kPieces], z1[kPieces], h0[MASKED ? kPieces : 1], h1[MASKED ? kPieces : 1];
+    };
+    auto load_step = [&](Step& q, int64_t r0) {
 #pragma unroll
-        for (int half = 0; half < 2 * kRowPasses; ++half) {
-            const int cv = cq + (half & 1) * 8;
-            const int64_t r = r0 + lr + (half >> 1) * 32;
-            qp[half] = make_uint4(0u, 0u, 0u, 0u);
-            qz[half] = qp[half];
-            if (MASKED) qh[half] = qp[half];
+        for (int i = 0; i < kPieces; ++i) {
+            const int cv = cq + (i % kChunkReps) * kChunkLanes;
+            const int64_t r = r0 + 2 * (rp + (i / kChunkReps) * 32);
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            q.p0[i] = q.p1[i] = q.z0[i] = q.z1[i] = zero;
+            if (MASKED) q.h0[i] = q.h1[i] = zero;
             if (r < r_end) {
-                if (cv * 8 < cg) qp[half] = *reinterpret_cast<const uint4*>(p + r * fin + c0 + cv * 8);
+                if (cv * 8 < cg) q.p0[i] = *reinterpret_cast<const uint4*>(p + r * fin + c0 + cv * 8);
                 if (cv * 8 < og) {
-                    qz[half] = *reinterpret_cast<const uint4*>(gh + r * fout + o0 + cv * 8);
-                    if (MASKED) qh[half] = *reinterpret_cast<const uint4*>(h + r * fout + o0 + cv * 8);
+                    q.z0[i] = *reinterpret_cast<const uint4*>(gh + r * fout + o0 + cv * 8);
+                    if (MASKED) q.h0[i] = *reinterpret_cast<const uint4*>(h + r * fout + o0 + cv * 8);
+                }
+            }
+            if (r + 1 < r_end) {
+                if (cv * 8 < cg) q.p1[i] = *reinterpret_cast<const uint4*>(p + (r + 1) * fin + c0 + cv * 8);
+                if (cv * 8 < og) {
+                    q.z1[i] = *reinterpret_cast<const uint4*>(gh + (r + 1) * fout + o0 + cv * 8);
+                    if (MASKED) q.h1[i] = *reinterpret_cast<const uint4*>(h + (r + 1) * fout + o0 + cv * 8);
                 }
             }
         }
     };
-    load_step(r_begin);
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+    uint32_t* pt32 = reinterpret_cast<uint32_t*>(pt);
+    uint32_t* zt32 = reinterpret_cast<uint32_t*>(zt);
+    constexpr int kTileLdw = kTileLd / 2;
+    auto write_pairs = [&](uint32_t* t32, int cv, int pair, const uint4 a, const uint4 b) {
+        const uint32_t wa[4] = {a.x, a.y, a.z, a.w};
+        const uint32_t wb[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int half = 0; half < 2 * kRowPasses; ++half) {
-            const int cv = cq + (half & 1) * 8;
-            const int tr = lr + (half >> 1) * 32;   // tile row
-            const uint4 z = MASKED ? mask_vec(qz[half], qh[half]) : qz[half];
-            const uint32_t wp[4] = {qp[half].x, qp[half].y, qp[half].z, qp[half].w};
-            const uint32_t wz[4] = {z.x, z.y, z.z, z.w};
+        for (int j = 0; j < 4; ++j) {
+            t32[(cv * 8 + 2 * j) * kTileLdw + pair] = (wa[j] & 0xffffu) | (wb[j] << 16);
+            t32[(cv * 8 + 2 * j + 1) * kTileLdw + pair] = (wa[j] >> 16) | (wb[j] & 0xffff0000u);
+        }
+    };
+    // one step: its rows into the tiles, the step after next requested into the registers just freed, product
+    auto do_step = [&](Step& q, int64_t r_next) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                pt[(cv * 8 + 2 * j) * kTileLd + tr] = (uint16_t)(wp[j] & 0xffffu);
-                pt[(cv * 8 + 2 * j + 1) * kTileLd + tr] = (uint16_t)(wp[j] >> 16);
-                zt[(cv * 8 + 2 * j) * kTileLd + tr] = (uint16_t)(wz[j] & 0xffffu);
-                zt[(cv * 8 + 2 * j + 1) * kTileLd + tr] = (uint16_t)(wz[j] >> 16);
-            }
+        for (int i = 0; i < kPieces; ++i) {
+            const int cv = cq + (i % kChunkReps) * kChunkLanes;
+            const int pair = rp + (i / kChunkReps) * 32;
+            write_pairs(pt32, cv, pair, q.p0[i], q.p1[i]);
+            write_pairs(zt32, cv, pair, MASKED ? mask_vec(q.z0[i], q.h0[i]) : q.z0[i],
+                        MASKED ? mask_vec(q.z1[i], q.h1[i]) : q.z1[i]);
         }
         __syncthreads();
-        if (r0 + kTileRows < r_end) load_step(r0 + kTileRows);   // in flight while this step is multiplied
+        if (r_next < r_end) load_step(q, r_next);
         if (wave_live) {
 #pragma unroll
             for (int ks = 0; ks < kTileRows / 16; ++ks) {
-                const uint4 a = *reinterpret_cast<const uint4*>(pt + (wave * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
+                const uint4 a = *reinterpret_cast<const uint4*>(pt + (cw * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
 #pragma unroll
-                for (int ob = 0; ob < 4; ++ob) {
-                    if (ob < oblocks) {
-                        const uint4 b = *reinterpret_cast<const uint4*>(zt + (ob * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
+                for (int ob = 0; ob < kGradOBlocks; ++ob) {
+                    if (ob0 + ob < oblocks) {
+                        const uint4 b = *reinterpret_cast<const uint4*>(zt + ((ob0 + ob) * 32 + l32) * kTileLd + ks * 16 + khalf * 8);
                         acc[ob] = mfma(a, b, acc[ob]);  // D[c][o]
                     }
                 }
             }
         }
         __syncthreads();
+    };
+    Step qa, qb;
+    load_step(qa, r_begin);
+    load_step(qb, r_begin + kTileRows);   // past r_end: zeros, nothing read
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += 2 * kTileRows) {
+        do_step(qa, r0 + 2 * kTileRows);
+        if (r0 + kTileRows < r_end) do_step(qb, r0 + 3 * kTileRows);
     }
     if (!wave_live) return;
     float* dst = partial + (int64_t)blockIdx.x * fin * fout;
 #pragma unroll
-    for (int ob = 0; ob < 4; ++ob) {
-        if (ob < oblocks) {
+    for (int ob = 0; ob < kGradOBlocks; ++ob) {
+        if (ob0 + ob < oblocks) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int c = c0 + wave * 32 + (i / 4) * 8 + khalf * 4 + (i % 4);
-                dst[(int64_t)c * fout + o0 + ob * 32 + l32] = acc[ob][i];
+                const int c = c0 + cw * 32 + (i / 4) * 8 + khalf * 4 + (i % 4);
+                dst[(int64_t)c * fout + o0 + (ob0 + ob) * 32 + l32] = acc[ob][i];
             }
         }
     }
 }
 
 // gw[e] = sum over blocks of partial[b][e], in double and in a fixed order: thread (q, j) of a
-// workgroup adds blocks q, q + 4, q + 8, ... for element e0 + j; the four sums of an element are
+// workgroup adds blocks q, q + 8, q + 16, ... for element e0 + j; the eight sums of an element are
 // then added in q order.
-constexpr int kReduceElems = 64;   // elements per workgroup
-constexpr int kReduceSlices = kThreads / kReduceElems;
+constexpr int kReduceElems = 32;   // elements per workgroup (one 128-byte line of every partial matrix)
+constexpr int kReduceSlices = kReduceThreads / kReduceElems;
 
-__global__ __launch_bounds__(kThreads) void weight_grad_reduce(const float* __restrict__ partial, int32_t nblocks,
+__global__ __launch_bounds__(kReduceThreads) void weight_grad_reduce(const float* __restrict__ partial, int32_t nblocks,
                                                                int32_t count, float* __restrict__ gw) {
     __shared__ double red[kReduceSlices][kReduceElems];
     const int j = threadIdx.x % kReduceElems, q = threadIdx.x / kReduceElems;
     const int e = blockIdx.x * kReduceElems + j;
     double s = 0.0;
     if (e < count) {
-#pragma unroll 8
+#pragma unroll 16
         for (int32_t b = q; b < nblocks; b += kReduceSlices) s += (double)partial[(int64_t)b * count + e];
     }
     red[q][j] = s;
@@ -336,32 +406,37 @@ __global__ __launch_bounds__(kThreads) void weight_grad_reduce(const float* __re
 // few partial matrices are written and read back.
 int32_t rows_per_block_for(int32_t n) {
     int64_t r = ceil_div(n > 0 ? n : 1, 256);
-    r = (r + kTileRows - 1) / kTileRows * kTileRows;
+    r = (r + 63) / 64 * 64;
     return (int32_t)(r < 128 ? 128 : r);
+}
+
+template <bool MASKED, bool TRANS_W, bool RELU, int KS, bool EXACT, int WAVES>
+void launch_dense_as(const void* a, const void* mask, const void* w, void* out, int32_t n, int32_t kdim, int32_t ndim,
+                     int32_t w_ld, int32_t ngroup, hipStream_t stream) {
+    // eight wavefronts per compute unit, each taking as many tiles in turn as that leaves it, but no more
+    // workgroups than blocks of rows
+    const int64_t blocks = ceil_div(n, (int64_t)32 * WAVES);
+    int64_t tiles = ceil_div(blocks, (int64_t)kDenseMaxGroups * (8 / WAVES));
+    tiles = tiles < 1 ? 1 : tiles;
+    const dim3 grid((unsigned)ceil_div(blocks, tiles), (unsigned)ceil_div(ndim, ngroup));
+    // streaming stores once the result is far larger than the caches (measured: 5 % at 4 M rows); below
+    // that the next kernel of a mini-batch step finds the rows in the caches if they are written normally
+    const int32_t stream_out = (int64_t)n * ndim * 2 > (64ll << 20) ? 1 : 0;
+    dense_rows<MASKED, TRANS_W, RELU, KS, EXACT, WAVES><<<grid, dim3(64 * WAVES), 0, stream>>>(
+        static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
+        static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles, stream_out);
 }
 
 template <bool MASKED, bool TRANS_W, bool RELU>
 void launch_dense(const void* a, const void* mask, const void* w, void* out, int32_t n, int32_t kdim,
                   int32_t ndim, int32_t w_ld, hipStream_t stream) {
     const int32_t ngroup = kdim > 128 ? 64 : 128;
-    int64_t tiles = ceil_div(n, (int64_t)kRowsPerBlock * 512);   // keep at least ~512 workgroups
-    tiles = tiles < 1 ? 1 : (tiles > 8 ? 8 : tiles);
-    const dim3 grid((unsigned)ceil_div(n, kRowsPerBlock * tiles), (unsigned)ceil_div(ndim, ngroup));
-    // streaming stores once the result is far larger than the caches (measured: 5 % at 4 M rows); below
-    // that the next kernel of a mini-batch step finds the rows in the caches if they are written normally
-    const int32_t stream_out = (int64_t)n * ndim * 2 > (64ll << 20) ? 1 : 0;
     if (kdim == 128 && ndim % 128 == 0)
-        dense_rows<MASKED, TRANS_W, RELU, 8, true><<<grid, dim3(kThreads), 0, stream>>>(
-            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
-            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles, stream_out);
+        launch_dense_as<MASKED, TRANS_W, RELU, 8, true, kDenseWaves>(a, mask, w, out, n, kdim, ndim, w_ld, ngroup, stream);
     else if (kdim <= 128)
-        dense_rows<MASKED, TRANS_W, RELU, 8, false><<<grid, dim3(kThreads), 0, stream>>>(
-            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
-            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles, stream_out);
+        launch_dense_as<MASKED, TRANS_W, RELU, 8, false, kDenseWaves>(a, mask, w, out, n, kdim, ndim, w_ld, ngroup, stream);
     else
-        dense_rows<MASKED, TRANS_W, RELU, kMaxF / 16, false><<<grid, dim3(kThreads), 0, stream>>>(
-            static_cast<const uint16_t*>(a), static_cast<const uint16_t*>(mask), static_cast<const uint16_t*>(w),
-            static_cast<uint16_t*>(out), n, kdim, ndim, w_ld, ngroup, (int32_t)tiles, stream_out);
+        launch_dense_as<MASKED, TRANS_W, RELU, kMaxF / 16, false, 4>(a, mask, w, out, n, kdim, ndim, w_ld, ngroup, stream);
 }
 
 }  // namespace
@@ -462,12 +537,12 @@ int32_t transform_impl(const char* who, bool static_scratch, int32_t mode, int32
             const uint16_t* p = static_cast<const uint16_t*>(d_P);
             const uint16_t* gh = static_cast<const uint16_t*>(d_gH);
             const uint16_t* h = static_cast<const uint16_t*>(d_H);
-            if (relu) weight_grad_partial<true><<<grid, dim3(kThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
-            else weight_grad_partial<false><<<grid, dim3(kThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
+            if (relu) weight_grad_partial<true><<<grid, dim3(kGradThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
+            else weight_grad_partial<false><<<grid, dim3(kGradThreads), 0, stream>>>(p, gh, h, partial, n, Fin, Fout, rpb);
             E2EG_LAUNCH_CHECK("weight_grad_partial");
         }
         const int32_t count = Fin * Fout;
-        weight_grad_reduce<<<dim3((unsigned)ceil_div(count, kReduceElems)), dim3(kThreads), 0, stream>>>(partial, blocks, count, d_gW);
+        weight_grad_reduce<<<dim3((unsigned)ceil_div(count, kReduceElems)), dim3(kReduceThreads), 0, stream>>>(partial, blocks, count, d_gW);
         E2EG_LAUNCH_CHECK("weight_grad_reduce");
     }
     return E2EG_OK;
