@@ -87,15 +87,13 @@ __global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restr
                                                        uint16_t* __restrict__ out, int32_t n,
                                                        int32_t kdim, int32_t ndim, int32_t w_ld,
                                                        int32_t ngroup, int32_t tiles, int32_t stream_out) {
-    __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][ldb]
+    __shared__ __attribute__((aligned(16))) uint16_t bt[kWeightLds];  // [ngroup][kdim + kPad]
     __shared__ __attribute__((aligned(16))) uint16_t ot[WAVES][16 * kOutLd];  // per wavefront: 16 result rows
-    // Layout of the weight tile: k contiguous per output column c.  Copied as it is (W already k-contiguous)
-    // the rows are padded by kPad, which spreads a wavefront's 16-byte reads of 32 columns over the banks.
-    // Transposed on the way in, and kdim a multiple of 64, the rows are not padded; instead the 16-byte
-    // groups of row c are stored at group index ^ swizzle(c), swizzle(c) = (c + c / 8) % 8: the reads stay
-    // spread, and so do the transposing 4-byte writes (see below), which padding alone cannot achieve.
-    const bool swz = TRANS_W && (EXACT || kdim % 64 == 0);
-    const int ldb = swz ? kdim : kdim + kPad;
+    // The weight tile: k contiguous per output column, rows padded by kPad elements, which spreads a
+    // wavefront's 16-byte reads of 32 columns over the banks.  (An unpadded tile with the 16-byte groups of
+    // column c stored at group index ^ (c + c / 8) % 8 was measured too: SQ_LDS_BANK_CONFLICT 0.55 of the
+    // LDS cycles against 0.23 for the padding.)
+    const int ldb = kdim + kPad;
     const int n0 = blockIdx.y * ngroup;
     const int ng = ndim - n0 < ngroup ? ndim - n0 : ngroup;
     const int lane = threadIdx.x & 63;
@@ -119,7 +117,6 @@ __global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restr
     };
     constexpr int kDenseThreads = 64 * WAVES;
     constexpr int kRowsPerBlock = 32 * WAVES;   // one 32-row MFMA tile per wavefront
-    const int swz0 = l32 + (l32 >> 3);   // swizzle of column nb * 32 + l32 is (swz0 + 4 nb) % 8
     const int64_t row_first = (int64_t)blockIdx.x * kRowsPerBlock + wave * 32 + l32;
     const int64_t row_step = (int64_t)gridDim.x * kRowsPerBlock;
     // tiles requested ahead of the one being multiplied (each holds KS, masked 2 KS, 16-byte registers)
@@ -128,15 +125,15 @@ __global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restr
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) load_rows(row_first + d * row_step, nxt_a[d], nxt_m[d]);   // in flight while the weight tile is staged
     if (TRANS_W) {
-        // A thread takes the same 8 columns of two consecutive rows of W (k = 2 kp, 2 kp + 1), 16 bytes
-        // each -- a wavefront reads whole 128-byte lines -- and writes, for each of the 8 columns, the pair
-        // as one 4-byte word into that column's row of the tile.  The 64 lanes of a store instruction hold
-        // 4 values of kp and 16 column chunks; the swizzle sends them to 32 different banks, two lanes each.
-        const int cvecs = ng / 8;
+        // Transposing.  A thread takes the same 8 columns of two consecutive rows of W (k = 2 kp, 2 kp + 1),
+        // 16 bytes each, and writes, for each of the 8 columns, the pair as one 4-byte word into that
+        // column's row of the tile.  Consecutive lanes hold consecutive kp: a store instruction fills
+        // consecutive banks.
+        const int cvecs = ng / 8, kpairs = kdim / 2;
         uint32_t* bt32 = reinterpret_cast<uint32_t*>(bt);
         const int ldw = ldb / 2;
-        for (int e = threadIdx.x; e < (kdim / 2) * cvecs; e += kDenseThreads) {
-            const int kp = e / cvecs, ch = e - kp * cvecs;
+        for (int e = threadIdx.x; e < kpairs * cvecs; e += kDenseThreads) {
+            const int ch = e / kpairs, kp = e - ch * kpairs;
             const uint16_t* src = w + (int64_t)(2 * kp) * w_ld + n0 + ch * 8;
             const uint4 q0 = *reinterpret_cast<const uint4*>(src);
             const uint4 q1 = *reinterpret_cast<const uint4*>(src + w_ld);
@@ -145,9 +142,8 @@ __global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restr
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = ch * 8 + 2 * j;
-                const int g0 = swz ? ((c + (c >> 3)) & 7) : 0, g1 = swz ? ((c + 1 + ((c + 1) >> 3)) & 7) : 0;
-                bt32[c * ldw + ((((kp >> 2) ^ g0) << 2) | (kp & 3))] = (w0[j] & 0xffffu) | (w1[j] << 16);
-                bt32[(c + 1) * ldw + ((((kp >> 2) ^ g1) << 2) | (kp & 3))] = (w0[j] >> 16) | (w1[j] & 0xffff0000u);
+                bt32[c * ldw + kp] = (w0[j] & 0xffffu) | (w1[j] << 16);
+                bt32[(c + 1) * ldw + kp] = (w0[j] >> 16) | (w1[j] & 0xffff0000u);
             }
         }
     } else {
@@ -188,8 +184,7 @@ __global__ __launch_bounds__(64 * WAVES) void dense_rows(const uint16_t* __restr
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
                 if (nb < nblocks) {
-                    const int grp = (ks * 2 + khalf) ^ (swz ? ((swz0 + 4 * nb) & 7) : 0);
-                    const uint4 b = *reinterpret_cast<const uint4*>(bt + (nb * 32 + l32) * ldb + grp * 8);
+                    const uint4 b = *reinterpret_cast<const uint4*>(bt + (nb * 32 + l32) * ldb + ks * 16 + khalf * 8);
                     acc[nb] = mfma(b, areg[ks], acc[nb]);  // D[out column][row]
                 }
             }
