@@ -61,6 +61,16 @@ def test_transform_fwd_bwd(dev, oracle, n, Fin, Fout, relu):
     assert comp <= DW_TOL, (comp, norm)
 
 
+@pytest.mark.parametrize("n,Fin,Fout", [(70001, 128, 128), (200000, 128, 128), (66000, 96, 160), (66000, 256, 256),
+                                         (131073, 64, 32), (300000, 128, 128)])
+def test_transform_many_rows(dev, oracle, n, Fin, Fout):
+    """Enough rows that a workgroup of the row kernels takes several blocks in turn (the last turn ragged)
+    and a workgroup of the weight-gradient kernel several steps (the last one partly empty); the largest
+    case has more than 64 MB of results, which leave through streaming stores."""
+    test_transform_fwd_bwd(dev, oracle, n, Fin, Fout, True)
+    progress(f"transform {n} x {Fin} x {Fout} checked in full")
+
+
 def test_minibatch_pipeline(dev, oracle):
     """Sampled two-hop subgraph: per layer P = A^ H, Z = P W, ReLU between layers (none after
     the last), then the full backward.  Each GPU stage is checked against the oracle applied to
