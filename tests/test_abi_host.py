@@ -69,6 +69,25 @@ def test_workspace_queries_are_pure_host_functions(B):
         assert q % 256 == 0
 
 
+def test_workspace_queries_at_the_largest_sizes_the_abi_accepts(B):
+    """nnz up to INT32_MAX: the sizes are computed in 64 bits (a wrapped product would fall below these
+    lower bounds, which count only the largest arrays each call needs)."""
+    n, nnz = 60_000_000, 2 ** 31 - 1
+    assert B.e2eg_sched_bytes(n, nnz) >= 12 * nnz                  # columns, node ids, scales per entry
+    assert B.e2eg_sched_weighted_bytes(n, nnz) >= 16 * nnz         # and values
+    assert B.e2eg_normalize_workspace_bytes(n, nnz) >= 16 * nnz    # two arrays of 8-byte sort keys
+    assert B.e2eg_propagate_workspace_bytes(n, nnz, B.E2EG_BF16, 128, 3) >= 2 * (n + 1) * 128 * 2   # two Z buffers
+    assert B.e2eg_propagate_workspace_bytes(n, nnz, B.E2EG_F32, 256, 3) >= 2 * (n + 1) * 256 * 4
+    n_users, n_items = 40_000_000, 20_000_000
+    E = (nnz - n) // 2                                             # 2 E + n stored entries
+    assert B.e2eg_build_csr_workspace_bytes(n_users, n_items, E) >= 16 * E
+    big = B.e2eg_layer_transform_workspace_bytes(B.E2EG_TRANSFORM_BWD, 2 ** 31 - 1, 256, 256, B.E2EG_BF16)
+    assert 256 * 256 * 4 * 250 <= big <= 256 * 256 * 4 * 260       # about 256 partial matrices whatever n
+    for k in (1, 2, 3):                                            # monotone in K
+        assert B.e2eg_propagate_workspace_bytes(n, nnz, B.E2EG_BF16, 128, k) <= \
+            B.e2eg_propagate_workspace_bytes(n, nnz, B.E2EG_BF16, 128, k + 1)
+
+
 FAKE = 0x1000  # non-null, 256-byte aligned; never dereferenced because validation fails first
 
 
