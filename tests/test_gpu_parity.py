@@ -156,6 +156,35 @@ def test_propagate_long_rows_feature_widths(dev, oracle, dtype, F):
     run_case(dev, oracle, c)
 
 
+def test_identical_addends_in_long_wide_fp32_rows(dev, oracle):
+    """The worst case of the fp32 sums: one item joined to thousands of users with one item each and no
+    self-loops, so that from the second layer on the item's row adds thousands of IDENTICAL values, and rows
+    of 528 bytes, which one lane group sums 512 entries at a time.  Adding a constant to a growing partial
+    sum rounds the same way every time: the error grows with the number of terms, not with its root.  Each
+    fp32 add loses at most 2^-24 of the partial sum, so a run of 512 loses at most 512 * 2^-24 = 3.1e-5 of
+    the abs-sum, runs are added in double, and every layer can add as much again: asserted K * 512 * 2^-24
+    (measured 7.2e-6 per layer of such sums, 1.2e-5 after K = 4)."""
+    nu, K, F = 9000, 4, 132
+    rng = np.random.default_rng(140)
+    users = np.unique(rng.integers(0, nu, 15000)).astype(np.int32)
+    items = np.zeros(users.size, dtype=np.int32)
+    g = dev.build_graph(nu, 1, torch.from_numpy(users).cuda(), torch.from_numpy(items).cuda(), add_self_loops=False)
+    row_ptr, col = oracle.build_csr(nu, 1, users, items, add_self_loops=False)
+    assert np.array_equal(g.col_idx.cpu().numpy(), col)
+    Xh, gh = make_features(nu + 1, F, 0.1, 140, "f32"), make_features(nu + 1, F, 1.0, 141, "f32")
+    H = dev.propagate_fwd(g, to_device(Xh, "f32"), K)
+    G0 = dev.propagate_bwd(g, to_device(gh, "f32"), K)
+    torch.cuda.synchronize()
+    bound = K * 512 * 2.0 ** -24
+    for got, ref, scale, what in (
+            (H, oracle.propagate_fwd(row_ptr, col, Xh, K)[K - 1],
+             oracle.propagate_fwd(row_ptr, col, np.abs(oracle.as_f64(Xh)), K)[K - 1], "fwd"),
+            (G0, oracle.propagate_bwd(row_ptr, col, gh, K),
+             oracle.propagate_bwd(row_ptr, col, np.abs(oracle.as_f64(gh)), K), "bwd")):
+        comp, norm = errors(to_f64(got), ref, scale)
+        assert comp <= bound and norm <= bound, (what, comp, norm, bound)
+
+
 def test_propagate_many_tiny_segments(dev, oracle):
     """A thousand popular items that each have one neighbour in every window of the node range and
     a dense run in one: the segment list is mostly one-entry segments, all dealt to one XCD, many
